@@ -1,0 +1,423 @@
+"""Pins of the speculative-sampling oracle against what the method fixes."""
+import itertools
+
+import numpy as np
+import pytest
+from scipy import stats
+
+from oracle import decoder as dec
+from oracle import metrics
+from oracle import spec_sampling as ss
+from paper_2404_08856_amd import synth
+
+
+def rand_dist(rng, V, conc=1.0):
+    return rng.dirichlet(np.full(V, conc)).astype(np.float32)
+
+
+def all_grid_uniforms(step):
+    """Every step-th point of the u grid j / 2^24 (float32, exact)."""
+    return (np.arange(0, 1 << 24, step, dtype=np.int64).astype(np.float32) * np.float32(2.0 ** -24))
+
+
+# --------------------------------------------------------------------------------------
+# accept rule
+# --------------------------------------------------------------------------------------
+
+def test_accept_probability_is_min_1_ratio_exhaustive_over_the_u_grid():
+    """P(accept) over ALL 2^24 grid uniforms equals min(1, T/D) to within the grid."""
+    cases = [(0.3, 0.6), (0.6, 0.3), (0.25, 0.25), (1e-4, 0.9), (0.0, 0.5), (0.5, 1.0), (0.123, 0.457)]
+    u = all_grid_uniforms(1)
+    for T_x, D_x in cases:
+        acc = (u * np.float32(D_x)) < np.float32(T_x)           # the oracle's test, vectorised
+        # spot-check that the vectorised form is the oracle's scalar function
+        for j in (0, 1, 12345, (1 << 24) - 1):
+            assert ss.accept_test(T_x, D_x, u[j]) == bool(acc[j])
+        want = ss.accept_probability(np.float32(T_x), np.float32(D_x))
+        assert abs(acc.mean() - want) <= 2.0 ** -23
+        assert abs(want - min(1.0, T_x / D_x)) < 1e-6
+
+
+def test_accept_edge_cases():
+    assert ss.accept_test(0.5, 0.5, np.float32(1 - 2.0 ** -24))       # T >= D > 0: always
+    assert ss.accept_test(0.7, 0.2, np.float32(0.999))
+    assert not ss.accept_test(0.0, 0.3, np.float32(0.0))              # T = 0: never
+    assert ss.accept_test(0.1, 0.0, np.float32(0.9))                  # D = 0 (cannot be drafted): iff T > 0
+    assert not ss.accept_test(0.0, 0.0, np.float32(0.0))
+
+
+def test_acceptance_rate_equals_sum_min_bruteforce():
+    """sum_x D(x) min(1, T/D) = sum_x min(T, D), against Monte-Carlo over the whole block step."""
+    rng = np.random.default_rng(0)
+    V = 6
+    T = rand_dist(rng, V)
+    D = rand_dist(rng, V)
+    want = float(np.minimum(T.astype(np.float64), D.astype(np.float64)).sum())
+    exact = sum(float(D[x]) * ss.accept_probability(T[x], D[x]) for x in range(V))
+    assert abs(exact - want) < 1e-7
+    N = 200000
+    u = synth.uniforms((N, 2), 1)
+    acc = 0
+    for i in range(N):
+        d = ss.sample_row(D, u[i, 0])
+        acc += ss.accept_test(T[d], D[d], u[i, 1])
+    se = np.sqrt(want * (1 - want) / N)
+    assert abs(acc / N - want) < 4 * se
+
+
+# --------------------------------------------------------------------------------------
+# residual and the output distribution
+# --------------------------------------------------------------------------------------
+
+def test_output_distribution_identity():
+    """D(x) min(1, T/D) + (1 - sum min) * max(0, T-D) / sum max(0, T-D) = T(x), per x."""
+    rng = np.random.default_rng(1)
+    for V in (2, 5, 16):
+        for _ in range(20):
+            T = rand_dist(rng, V)
+            D = rand_dist(rng, V)
+            r = ss.residual(T, D).astype(np.float64)
+            assert np.all(r >= 0)
+            p_acc = np.array([D[x] * ss.accept_probability(T[x], D[x]) for x in range(V)], dtype=np.float64)
+            p_rej = 1.0 - p_acc.sum()
+            out = p_acc + p_rej * r / r.sum()
+            assert np.max(np.abs(out - T.astype(np.float64))) < 1e-6
+
+
+def test_residual_is_elementwise_positive_part():
+    T = np.array([0.5, 0.2, 0.3, 0.0], dtype=np.float32)
+    D = np.array([0.1, 0.6, 0.3, 0.0], dtype=np.float32)
+    r = ss.residual(T, D)
+    assert r.dtype == np.float32
+    assert np.array_equal(r, np.array([np.float32(0.5) - np.float32(0.1), 0, 0, 0], dtype=np.float32))
+
+
+def exact_block_output_distribution(T, D):
+    """Exact law of the first emitted token for gamma = 1, by enumerating the
+    draft token and integrating the two uniforms analytically."""
+    V = len(T)
+    T64, D64 = T.astype(np.float64), D.astype(np.float64)
+    out = np.zeros(V)
+    r = np.maximum(0.0, T64 - D64)
+    for d in range(V):
+        a = min(1.0, T64[d] / D64[d]) if D64[d] > 0 else 0.0
+        out[d] += D64[d] * a
+        out += D64[d] * (1 - a) * r / r.sum()
+    return out
+
+
+def test_chi_square_of_sampled_output_against_target():
+    """One block with gamma = 1 on a tiny vocabulary: the first emitted token
+    follows T (the guarantee of Section 2.1), chi-square at N = 1e5."""
+    rng = np.random.default_rng(2)
+    V = 12
+    T = rand_dist(rng, V)
+    D = rand_dist(rng, V)
+    assert np.max(np.abs(exact_block_output_distribution(T, D) - T)) < 1e-6
+    Tb = rand_dist(rng, V)                      # bonus row (unused for the first token)
+    N = 100000
+    u = synth.uniforms((N, 3), 7)
+    counts = np.zeros(V)
+    n_acc = 0
+    for i in range(N):
+        d = ss.sample_row(D, u[i, 0])
+        k, y = ss.speculative_accept(np.stack([T, Tb]), D[None], [d], u[i, 1:3])
+        first = d if k == 1 else y
+        counts[first] += 1
+        n_acc += k
+    chi = stats.chisquare(counts, T.astype(np.float64) / T.astype(np.float64).sum() * N)
+    assert chi.pvalue > 1e-3, chi
+    # and it does NOT follow the draft distribution (the test has power)
+    assert stats.chisquare(counts, D.astype(np.float64) / D.astype(np.float64).sum() * N).pvalue < 1e-6
+    want = float(np.minimum(T, D).astype(np.float64).sum())
+    assert abs(n_acc / N - want) < 4 * np.sqrt(want * (1 - want) / N)
+
+
+def test_rejected_output_follows_normalised_residual():
+    rng = np.random.default_rng(3)
+    V = 8
+    T = rand_dist(rng, V)
+    D = rand_dist(rng, V)
+    r = ss.residual(T, D).astype(np.float64)
+    N = 60000
+    u = synth.uniforms((N, 3), 11)
+    counts = np.zeros(V)
+    for i in range(N):
+        d = ss.sample_row(D, u[i, 0])
+        k, y = ss.speculative_accept(np.stack([T, T]), D[None], [d], u[i, 1:3])
+        if k == 0:
+            counts[y] += 1
+    support = r > 0
+    assert counts[~support].sum() == 0
+    chi = stats.chisquare(counts[support], r[support] / r.sum() * counts.sum())
+    assert chi.pvalue > 1e-3
+
+
+def test_identical_distributions_accept_everything_and_bonus_follows_last_row():
+    rng = np.random.default_rng(4)
+    V, gamma = 10, 4
+    N = 20000
+    u = synth.uniforms((N, 2 * gamma + 1), 5)
+    T = np.stack([rand_dist(rng, V) for _ in range(gamma + 1)])
+    counts = np.zeros(V)
+    for i in range(N):
+        d = [ss.sample_row(T[j], u[i, j]) for j in range(gamma)]
+        k, y = ss.speculative_accept(T, T[:gamma], d, u[i, gamma:])
+        assert k == gamma                                     # tau = gamma + 1 exactly
+        counts[y] += 1
+    assert stats.chisquare(counts, T[gamma].astype(np.float64) / T[gamma].astype(np.float64).sum() * N).pvalue > 1e-3
+
+
+def test_disjoint_supports_reject_first_and_resample_from_target():
+    V, gamma = 8, 3
+    T = np.zeros((gamma + 1, V), dtype=np.float32)
+    D = np.zeros((gamma, V), dtype=np.float32)
+    T[:, :4] = np.array([0.1, 0.2, 0.3, 0.4], dtype=np.float32)
+    D[:, 4:] = 0.25
+    N = 20000
+    u = synth.uniforms((N, 2 * gamma + 1), 6)
+    counts = np.zeros(V)
+    for i in range(N):
+        d = [ss.sample_row(D[j], u[i, j]) for j in range(gamma)]
+        assert all(x >= 4 for x in d)
+        k, y = ss.speculative_accept(T, D, d, u[i, gamma:])
+        assert k == 0
+        counts[y] += 1
+    assert counts[4:].sum() == 0
+    assert stats.chisquare(counts[:4], np.array([0.1, 0.2, 0.3, 0.4]) * N).pvalue > 1e-3
+
+
+def test_sequential_verification_stops_at_first_rejection():
+    V, gamma = 4, 4
+    T = np.full((gamma + 1, V), 0.25, dtype=np.float32)
+    D = np.full((gamma, V), 0.25, dtype=np.float32)
+    T[2] = np.array([0.0, 0.5, 0.25, 0.25], dtype=np.float32)   # token 0 impossible under the target at j = 3
+    d = [0, 0, 0, 0]
+    u = np.zeros(gamma + 1, dtype=np.float32)
+    k, y = ss.speculative_accept(T, D, d, u)
+    assert k == 2                                               # later positions are not looked at
+    assert y == 1                                               # residual max(0, T-D) = [0, .25, 0, 0]
+
+
+# --------------------------------------------------------------------------------------
+# fixed-point sampler
+# --------------------------------------------------------------------------------------
+
+def test_fixed_point_weights_are_exact_truncations():
+    r = np.array([0.0, 1.0, 0.5, 2.0 ** -32, 2.0 ** -33, 0.3], dtype=np.float32)
+    w = ss.fixed_point_weights(r)
+    assert w.dtype == np.uint64
+    assert list(map(int, w[:5])) == [0, 1 << 32, 1 << 31, 1, 0]
+    assert int(w[5]) == int(np.floor(float(np.float32(0.3)) * 2 ** 32))
+
+
+def test_sampler_interval_lengths_proportional_to_weights_exhaustive():
+    """Over ALL 2^24 uniforms the count of each outcome is within 1 of
+    2^24 * w(x) / S, the outcome is monotone in u, and never has w = 0."""
+    rng = np.random.default_rng(5)
+    for V in (2, 3, 8):
+        r = rand_dist(rng, V)
+        r[rng.integers(V)] = 0.0                            # a hole in the support
+        r = (r * np.float32(0.37)).astype(np.float32)       # unnormalised on purpose
+        w = ss.fixed_point_weights(r).astype(np.float64)
+        # vectorised restatement over the full grid, anchored to the scalar oracle below
+        S = int(w.sum())
+        k_u = np.arange(1 << 24, dtype=np.uint64)
+        thr = (k_u * np.uint64(S)) >> np.uint64(24)
+        y = np.searchsorted(np.cumsum(w.astype(np.uint64)), thr, side="right")
+        counts = np.bincount(y, minlength=V)
+        assert np.all(np.abs(counts - (1 << 24) * w / S) <= 1.0)
+        assert np.all(np.diff(y) >= 0)
+        assert counts[w == 0].sum() == 0
+        for j in list(range(0, 1 << 24, 999983)) + [(1 << 24) - 1]:
+            assert ss.sample_fixed_point(r, np.float32(j * 2.0 ** -24)) == y[j]
+
+
+def test_sampler_bruteforce_tiny():
+    """Hand-checkable case: weights 1/4, 0, 1/2, 1/4."""
+    r = np.array([0.25, 0.0, 0.5, 0.25], dtype=np.float32)
+    f = lambda u: ss.sample_fixed_point(r, np.float32(u))
+    assert f(0.0) == 0 and f(0.2499999) == 0
+    assert f(0.25) == 2 and f(0.7499999) == 2
+    assert f(0.75) == 3 and f(1 - 2.0 ** -24) == 3
+    assert ss.sample_fixed_point(np.zeros(4, dtype=np.float32), np.float32(0.3)) is None
+    assert ss.sample_fixed_point(np.full(4, 2.0 ** -34, dtype=np.float32), np.float32(0.3)) is None
+
+
+def test_residual_with_no_representable_mass_falls_back_to_target_row():
+    T = np.array([0.5, 0.5, 0, 0], dtype=np.float32)
+    D = T.copy()
+    D[0] = np.float32(0.5) + np.float32(2.0 ** -24)          # barely above T: can be rejected, residual = 0
+    u = np.array([np.float32(1 - 2.0 ** -24), np.float32(0.75)], dtype=np.float32)
+    assert not ss.accept_test(T[0], D[0], u[0])
+    k, y = ss.speculative_accept(np.stack([T, T]), D[None], [0], u)
+    assert k == 0 and y == 1                                   # drawn from T itself with u = 0.75
+
+
+# --------------------------------------------------------------------------------------
+# softmax / temperature / greedy
+# --------------------------------------------------------------------------------------
+
+def test_softmax_probs_matches_library_and_temperature():
+    rng = np.random.default_rng(6)
+    lg = rng.standard_normal((3, 50)) * 2
+    from scipy.special import softmax
+    for temp in (1.0, 0.7, 2.0):
+        got = ss.softmax_probs(lg, temp)
+        assert got.dtype == np.float32
+        assert np.max(np.abs(got - softmax(lg / temp, axis=-1))) < 1e-7
+    hot = ss.softmax_probs(np.array([[0.1, 3.0, 3.0, -1.0]]), 0.0)
+    assert np.array_equal(hot, np.array([[0, 1, 0, 0]], dtype=np.float32))    # lowest index on ties
+
+
+def test_greedy_block_reduces_to_argmax_rules():
+    rng = np.random.default_rng(7)
+    V, gamma = 9, 4
+    for _ in range(200):
+        lt = rng.standard_normal((gamma + 1, V))
+        ld = lt[:gamma] + rng.standard_normal((gamma, V)) * 0.7
+        T = ss.softmax_probs(lt, 0.0)
+        D = ss.softmax_probs(ld, 0.0)
+        d = [ss.sample_row(D[j], rng.random()) for j in range(gamma)]
+        assert d == list(np.argmax(ld, axis=-1))
+        u = rng.random(gamma + 1).astype(np.float32)
+        k, y = ss.speculative_accept(T, D, d, u)
+        want_k = 0
+        while want_k < gamma and d[want_k] == int(np.argmax(lt[want_k])):
+            want_k += 1
+        assert k == want_k and y == int(np.argmax(lt[k]))
+
+
+def make_pair(seed=0):
+    ts, ds = synth.SHAPES["tiny_target"], synth.SHAPES["tiny_draft"]
+    tw = synth.weights_to_numpy(synth.make_weights(ts, seed))
+    dw = synth.weights_to_numpy(synth.make_weights(ds, seed + 1))
+    tc = dec.DecoderConfig(ts.n_layers, ts.d_model, ts.n_heads, ts.head_dim, ts.d_ffn, ts.vocab)
+    dc = dec.DecoderConfig(ds.n_layers, ds.d_model, ds.n_heads, ds.head_dim, ds.d_ffn, ds.vocab)
+    return (tc, tw), (dc, dw)
+
+
+def aligned_pair(seed=0):
+    """A draft that agrees with the target often: the target itself with
+    slightly perturbed LM head (so that acceptance is neither 0 nor 1)."""
+    target, _ = make_pair(seed)
+    tc, tw = target
+    dw = dict(tw)
+    rng = np.random.default_rng(seed)
+    lm = dec.to_f64(tw["lm_head"]) + rng.standard_normal(tw["lm_head"].shape) * 0.004
+    dw["lm_head"] = lm.astype(np.float32)
+    return target, (tc, dw)
+
+
+@pytest.mark.parametrize("gamma", [1, 3, 4])
+def test_greedy_speculative_equals_greedy_autoregressive(gamma):
+    """Greedy decoding: the speculative output is the target's own
+    autoregressive output token for token (Section 4, Decoding) -- with an
+    unrelated draft (mostly rejections) and with an aligned draft (mixed)."""
+    n_new = 24
+    img = synth.image_rows(8, 256, 0)
+    toks = synth.text_tokens(8, 1024, 0)
+    for pair, img in ((make_pair(), img), (aligned_pair(), None)):   # aligned: same (text-only) context
+        target, draft = pair
+        u0 = np.float32(0.5)
+        ud = synth.uniforms((n_new, gamma), 1)
+        ua = synth.uniforms((n_new, gamma + 1), 2)
+        got = ss.spd_generate(target, draft, img, toks, gamma, n_new, 0.0, u0, ud, ua)
+        ref = ss.ar_generate(target, img, toks, n_new, 0.0, synth.uniforms((n_new,), 3))
+        assert got["tokens"] == ref
+        ks = [b["k"] for b in got["blocks"]]
+        assert all(0 <= k <= gamma for k in ks)
+    assert max(ks) > 0 and min(ks) < gamma          # the aligned pair exercises both branches
+
+
+def test_text_only_draft_ignores_image_but_target_does_not():
+    """The draft conditions on text only (Section 3): its proposals given the
+    same committed tokens do not depend on the image rows; the target's
+    distributions do."""
+    target, draft = make_pair()
+    toks = synth.text_tokens(8, 1024, 0)
+    gamma, n_new = 3, 4
+    ud = synth.uniforms((n_new, gamma), 1)
+    ua = synth.uniforms((n_new, gamma + 1), 2)
+    a = ss.spd_generate(target, draft, synth.image_rows(8, 256, 0), toks, gamma, n_new, 1.0, np.float32(0.3), ud, ua)
+    b = ss.spd_generate(target, draft, synth.image_rows(8, 256, 1), toks, gamma, n_new, 1.0, np.float32(0.3), ud, ua)
+    assert not np.array_equal(a["blocks"][0]["T"], b["blocks"][0]["T"])
+    if a["tokens"][0] == b["tokens"][0]:               # same first committed token -> same draft rows
+        assert np.array_equal(a["blocks"][0]["D"], b["blocks"][0]["D"])
+    # direct statement: draft forward takes text tokens only
+    dc, dw = draft
+    c = dec.KVCache(dc, 16)
+    l1 = dec.forward_tokens(dc, dw, c, toks)
+    assert l1.shape == (8, 1024)
+
+
+def test_sampled_speculative_first_tokens_follow_target_distribution():
+    """Temperature 1 on the tiny model pair: over many uniform draws the
+    first token emitted by a block is distributed as the target's row."""
+    target, draft = aligned_pair()
+    (tc, tw), (dc, dw) = target, draft
+    toks = synth.text_tokens(8, 1024, 0)
+    t_cache = dec.KVCache(tc, 32)
+    d_cache = dec.KVCache(dc, 32)
+    dec.forward_tokens(tc, tw, t_cache, toks[:-1])
+    dec.forward_tokens(dc, dw, d_cache, toks[:-1])
+    T0 = ss.softmax_probs(dec.forward_tokens(tc, tw, t_cache, toks[-1:])[0], 1.0)
+    D0 = ss.softmax_probs(dec.forward_tokens(dc, dw, d_cache, toks[-1:])[0], 1.0)
+    N = 50000
+    u = synth.uniforms((N, 3), 9)
+    first = np.empty(N, dtype=np.int64)
+    for i in range(N):
+        d = ss.sample_row(D0, u[i, 0])
+        k, y = ss.speculative_accept(np.stack([T0, T0]), D0[None], [d], u[i, 1:])
+        first[i] = d if k == 1 else y
+    # pool the 1024-token vocabulary into 16 equal-probability-ish bins by target rank
+    order = np.argsort(-T0.astype(np.float64))
+    bins = np.minimum((np.cumsum(T0.astype(np.float64)[order]) * 16).astype(int), 15)
+    bin_of = np.empty(1024, dtype=int)
+    bin_of[order] = bins
+    obs = np.bincount(bin_of[first], minlength=16).astype(float)
+    exp = np.bincount(bin_of, weights=T0.astype(np.float64), minlength=16)
+    exp = exp / exp.sum() * N
+    keep = exp > 5
+    assert stats.chisquare(obs[keep], exp[keep] / exp[keep].sum() * obs[keep].sum()).pvalue > 1e-3
+
+
+# --------------------------------------------------------------------------------------
+# metrics
+# --------------------------------------------------------------------------------------
+
+def test_block_efficiency_closed_form_iid():
+    """iid acceptance alpha: E[tau] = (1 - alpha^(gamma+1)) / (1 - alpha); tau <= gamma + 1."""
+    gamma, V = 4, 5
+    T = np.array([0.4, 0.3, 0.2, 0.1, 0.0], dtype=np.float32)
+    D = np.array([0.1, 0.2, 0.3, 0.2, 0.2], dtype=np.float32)
+    alpha = float(np.minimum(T, D).astype(np.float64).sum())
+    Ts = np.stack([T] * (gamma + 1))
+    Ds = np.stack([D] * gamma)
+    N = 40000
+    u = synth.uniforms((N, 2 * gamma + 1), 13)
+    per_block = []
+    for i in range(N):
+        d = [ss.sample_row(D, u[i, j]) for j in range(gamma)]
+        k, _ = ss.speculative_accept(Ts, Ds, d, u[i, gamma:])
+        per_block.append(k + 1)
+    tau = metrics.block_efficiency(per_block)
+    want = metrics.expected_block_efficiency_iid(alpha, gamma)
+    assert abs(want - sum(alpha ** i for i in range(gamma + 1))) < 1e-12
+    assert max(per_block) <= gamma + 1
+    assert abs(tau - want) < 4 * np.std(per_block) / np.sqrt(N)
+    assert metrics.expected_block_efficiency_iid(1.0, gamma) == gamma + 1
+
+
+def test_mbsu_reading_reproduces_the_papers_scale():
+    """The reported 2.37x with c = 115M/7B needs tau ~ 2.5 under
+    tau / (c gamma + 1); the form with a factor c in the numerator could
+    never exceed 1 for c < 1/(gamma+1)..."""
+    c = 115e6 / 7e9
+    for gamma in (3, 5):
+        tau = 2.37 * (c * gamma + 1)
+        assert 1.0 < tau <= gamma + 1
+        assert abs(metrics.mbsu(tau, c, gamma) - 2.37) < 1e-12
+        assert c * (gamma + 1) / (c * gamma + 1) < 1.0          # upper bound of the printed form
+    assert metrics.mbsu(4.0, 0.0, 3) == 4.0                      # free draft: speed-up = tau
+    assert metrics.mbsu(1.0, 1.0, 1) == 0.5                      # draft as costly as target, nothing accepted
