@@ -1,0 +1,188 @@
+/*
+ * spd.h -- C ABI of the MI355X (gfx950) speculative-decoding hot path.
+ *
+ * The library implements the data-parallel part of speculative decoding (SPD)
+ * for a LLaVA-style multimodal LLM, after "On Speculative Decoding for
+ * Multimodal Large Language Models" (arXiv 2404.08856):
+ *
+ *   - the target verification step: ONE forward pass of a LLaMA-architecture
+ *     decoder over the gamma+1 tokens [t, d_1..d_gamma] against a KV cache that
+ *     already holds the image-embedding prefix V_1..V_m and the text prefix
+ *     X_1..X_n (Section 2.1; Section 2.2, Eq. 1; Section 3);
+ *   - the draft model's autoregressive steps (Section 2.1; text-only draft,
+ *     Section 3) -- the same kernels at a smaller shape;
+ *   - the accept/reject rule min{1, T/D} and the residual resample from
+ *     max(0, T - D) (Section 2.1), plus the bonus token on full acceptance
+ *     (implied by the maximum block efficiency gamma+1, Section 4 Metrics).
+ *
+ * Notation: T(x) = target probability, D(x) = draft probability (the paper
+ * writes q and p; other texts swap the letters).
+ *
+ * Conventions
+ *   - Every function returns an int32 status (SPD_OK = 0, negative = error) and
+ *     never throws.  spd_last_error() returns a static description of the last
+ *     error of the calling thread.
+ *   - Pointers are DEVICE pointers unless the name starts with h_ (host).
+ *   - All device work is enqueued on the caller's hipStream_t, passed as void*
+ *     (NULL = the default stream).  No call synchronises the device.
+ *   - The library allocates no device memory: weights (packed), KV cache and
+ *     workspace live in caller-owned buffers whose sizes spd_model_bytes()
+ *     reports.  The model borrows them until spd_model_destroy().
+ *   - Shapes: d_model % 32 == 0, head_dim in {64, 128}, (n_heads*head_dim) % 16
+ *     == 0, d_ffn % 8 == 0, vocab % 16 == 0, rows per call (n_seqs * M) <= 64,
+ *     M <= 8.  Violations return SPD_ERR_SHAPE before anything is launched.
+ */
+#ifndef SPD_H
+#define SPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPD_OK               0
+#define SPD_ERR_INVALID_ARG (-1)
+#define SPD_ERR_SHAPE       (-2)
+#define SPD_ERR_CAPACITY    (-3)   /* KV cache / workspace / row limit exceeded */
+#define SPD_ERR_HIP         (-4)   /* a HIP runtime call failed; see spd_last_error() */
+
+#define SPD_MAX_ROWS         64    /* rows (n_seqs * M) per forward call          */
+#define SPD_MAX_M             8    /* new tokens per sequence per forward call    */
+
+/* flags of spd_speculative_accept */
+#define SPD_TARGET_IS_PROBS  1u    /* target rows are probabilities, not logits   */
+#define SPD_DRAFT_IS_PROBS   2u    /* draft rows are probabilities, not logits    */
+
+typedef struct spd_model spd_model;
+
+/* Shape of a LLaMA-architecture decoder (Appendix A.1, Table 1) + capacities. */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+    float   rms_eps;           /* RMSNorm epsilon (inside the square root)        */
+    float   rope_theta;        /* RoPE base; pair (i, i+head_dim/2), freq theta^(-2i/head_dim) */
+    int32_t tied_embeddings;   /* 1: LM head = embedding table                    */
+    int32_t max_seqs;          /* sequences the KV cache holds                    */
+    int32_t max_positions;     /* positions per sequence the KV cache holds       */
+} spd_model_config;
+
+/* Unpacked weights, device memory, row-major [out_features, in_features],
+ * bfloat16 matrices and float32 norm gains.  The per-layer members are HOST
+ * arrays of n_layers device pointers.  Only read during spd_model_create (and
+ * the work it enqueues): once that work has finished the caller may free them. */
+typedef struct {
+    const void  *embed;              /* bf16 [vocab, d_model]                      */
+    const void  *lm_head;            /* bf16 [vocab, d_model]; NULL if tied        */
+    const float *final_norm;         /* f32  [d_model]                             */
+    const float *const *attn_norm;   /* f32  [d_model] per layer                   */
+    const void  *const *wq;          /* bf16 [n_heads*head_dim, d_model]           */
+    const void  *const *wk;
+    const void  *const *wv;
+    const void  *const *wo;          /* bf16 [d_model, n_heads*head_dim]           */
+    const float *const *mlp_norm;    /* f32  [d_model]                             */
+    const void  *const *w_gate;      /* bf16 [d_ffn, d_model]                      */
+    const void  *const *w_up;        /* bf16 [d_ffn, d_model]                      */
+    const void  *const *w_down;      /* bf16 [d_model, d_ffn]                      */
+} spd_weights;
+
+/* Description of the last error on this thread ("" if none).  Host pointer,
+ * valid until the next failing call on the same thread. */
+const char *spd_last_error(void);
+
+/* Sizes (bytes) of the three caller-owned device buffers of a model:
+ * packed weights (matrices re-tiled for the matrix cores + gains + embedding
+ * table), KV cache (bf16, K after RoPE and V, all layers) and workspace. */
+int32_t spd_model_bytes(const spd_model_config *h_cfg, size_t *h_packed_bytes,
+                        size_t *h_kv_bytes, size_t *h_workspace_bytes);
+
+/* Builds a model (target or draft) over caller-owned buffers: enqueues the
+ * re-tiling of every matrix of *h_weights into `packed`, the RoPE table and the
+ * clearing of the workspace on `stream`.  All KV lengths start at 0.
+ * Errors: SPD_ERR_SHAPE (unsupported shape), SPD_ERR_CAPACITY (a buffer is
+ * smaller than spd_model_bytes says), SPD_ERR_INVALID_ARG (NULL/misaligned;
+ * buffers must be 256-byte aligned), SPD_ERR_HIP. */
+int32_t spd_model_create(const spd_model_config *h_cfg, const spd_weights *h_weights,
+                         void *packed, size_t packed_bytes, void *kv_cache, size_t kv_bytes,
+                         void *workspace, size_t workspace_bytes, void *stream,
+                         spd_model **h_out);
+
+int32_t spd_model_destroy(spd_model *model);
+
+/* Sets the number of valid KV positions of sequences 0..n_seqs-1 (rollback
+ * after a rejection, reset to 0, ...).  Host-side bookkeeping only: positions
+ * >= the new length are simply overwritten by later calls.
+ * Errors: SPD_ERR_CAPACITY if a length exceeds max_positions or n_seqs exceeds
+ * max_seqs, SPD_ERR_INVALID_ARG on negative values. */
+int32_t spd_kv_set_len(spd_model *model, const int32_t *h_len_per_seq, int32_t n_seqs);
+int32_t spd_kv_get_len(const spd_model *model, int32_t *h_len_per_seq, int32_t n_seqs);
+
+/* Not hot: feeds n_rows input-embedding rows (float32 [n_rows, d_model],
+ * e.g. [V_1..V_m ; E[X_1..X_n]] for the target, Section 2.2 Eq. 1) to sequence
+ * `seq` starting at its current KV length, appending their K, V.  If
+ * last_logits != NULL it receives the float32 logits [vocab] of the last row.
+ * Runs the same kernels as the verify step, 8 rows per pass. */
+int32_t spd_prefill(spd_model *model, int32_t seq, const float *embeds, int32_t n_rows,
+                    float *last_logits, void *stream);
+
+/* Same, from token ids (int32 [n_rows]); the text-only draft's prefill (Section 3). */
+int32_t spd_prefill_tokens(spd_model *model, int32_t seq, const int32_t *tokens, int32_t n_rows,
+                           float *last_logits, void *stream);
+
+/* HOT.  One decoder forward over M new tokens for each of sequences
+ * 0..n_seqs-1, starting at each sequence's current KV length: the single
+ * target call that yields T_1..T_{gamma+1} when tokens = [t, d_1..d_gamma] and
+ * M = gamma+1 (Section 2.1, Section 3); M = 1 is plain autoregressive decoding.
+ * tokens: int32 [n_seqs, M].  logits_out: float32 [n_seqs, M, vocab]; row j is
+ * the distribution of the token after input j.  Appends the M keys/values of
+ * every sequence and advances its KV length by M (roll back with
+ * spd_kv_set_len).  Errors: SPD_ERR_SHAPE (M > 8 or n_seqs*M > 64),
+ * SPD_ERR_CAPACITY (KV overflow; nothing is launched). */
+int32_t spd_verify_forward(spd_model *target, const int32_t *tokens, int32_t n_seqs, int32_t M,
+                           float *logits_out, void *stream);
+
+/* HOT.  One draft decode step (Section 2.1: d_j ~ D(. | X_1:n, d_1..d_{j-1});
+ * Section 3: text-only conditioning): feeds n_in (1 or 2) tokens per sequence
+ * -- 2 after a fully accepted block, when the draft has not yet consumed
+ * d_gamma -- and from the logits of the last one writes
+ *   D_row_out  float32 [n_seqs, vocab]  softmax(logits / temperature)
+ *   token_out  int32   [n_seqs]         drawn from D_row with the fixed-point
+ *                                        inverse-CDF sampler and u_draft[n_seqs];
+ * temperature 0: D_row is one-hot at the argmax (lowest index on ties).
+ * tokens_in: int32 [n_seqs, n_in].  Advances the draft's KV lengths by n_in. */
+int32_t spd_draft_step(spd_model *draft, const int32_t *tokens_in, int32_t n_seqs, int32_t n_in,
+                       float temperature, const float *u_draft, float *D_row_out,
+                       int32_t *token_out, void *stream);
+
+/* HOT.  Speculative sampling for n_seqs sequences x gamma drafted tokens
+ * (Section 2.1; Section 3 for the multimodal conditioning of T).
+ *   target        float32 [n_seqs, gamma+1, vocab]  logits, or probabilities with SPD_TARGET_IS_PROBS
+ *   draft         float32 [n_seqs, gamma, vocab]    logits, or probabilities with SPD_DRAFT_IS_PROBS
+ *   draft_tokens  int32   [n_seqs, gamma]
+ *   u             float32 [n_seqs, gamma+1] on the grid j/2^24: u[:, :gamma] drive the
+ *                 accept tests, u[:, gamma] the replacement / bonus draw
+ * Per sequence: k = number of leading j with u_j * D_j(d_j) < T_j(d_j) (float32
+ * multiply and compare: accept probability min{1, T/D}); then the next token y
+ * is drawn from max(0, T_{k+1} - D_{k+1}) normalised if k < gamma, else from
+ * T_{gamma+1}, with the fixed-point inverse-CDF sampler: w(x) = floor(r(x) 2^32),
+ * threshold = floor(u 2^24 * sum w / 2^24), y = first x whose running sum
+ * exceeds it (if the residual has no representable mass: same draw from T_{k+1}).
+ * temperature scales logits (softmax(l / temperature)); temperature 0 = greedy
+ * (one-hot rows, lowest index on ties); it is ignored for probability inputs.
+ *   n_accepted_out  int32 [n_seqs]      k
+ *   next_token_out  int32 [n_seqs]      y
+ *   accept_prob_out float32 [n_seqs, gamma] or NULL: min{1, T_j(d_j)/D_j(d_j)}
+ *   workspace       float32 scratch, >= spd_accept_workspace_bytes(...) bytes
+ * Errors: SPD_ERR_INVALID_ARG (NULL, gamma < 1, temperature < 0),
+ * SPD_ERR_CAPACITY (workspace too small). */
+int32_t spd_accept_workspace_bytes(int32_t n_seqs, int32_t gamma, int32_t vocab, size_t *h_bytes);
+int32_t spd_speculative_accept(const float *target, const float *draft, const int32_t *draft_tokens,
+                               const float *u, int32_t n_seqs, int32_t gamma, int32_t vocab,
+                               float temperature, uint32_t flags, int32_t *n_accepted_out,
+                               int32_t *next_token_out, float *accept_prob_out,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPD_H */

@@ -1,0 +1,70 @@
+// Internal helpers shared by the HIP translation units of libspd (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spd {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+constexpr int kWave = 64;
+constexpr int kTileN = 16;     // weight rows per matrix-core tile
+constexpr int kStepK = 32;     // contraction elements per matrix-core step
+constexpr int kMaxM = 8;       // rows per row group (hi/lo halves fill the 16 columns)
+constexpr int kMaxRows = 64;
+constexpr int kMaxGroups = kMaxRows / kMaxM;
+
+// float32 -> bfloat16 bits, round to nearest even (NaN -> quiet NaN).
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t b = __float_as_uint(f);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return (uint16_t)(b >> 16);
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) {
+    return __uint_as_float(((uint32_t)h) << 16);
+}
+// two bf16 packed in a uint32 (element 0 in the low half)
+__device__ __forceinline__ float bf16_lo(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
+
+// Split x into a bf16 head and a bf16 tail: x ~= hi + lo with ~16 significant bits.
+__device__ __forceinline__ void split_hi_lo(float x, uint16_t &hi, uint16_t &lo) {
+    hi = f32_to_bf16_bits(x);
+    lo = f32_to_bf16_bits(x - bf16_bits_to_f32(hi));
+}
+
+// ---------------------------------------------------------------------------------
+// Operand layouts for v_mfma_f32_16x16x32_bf16 (A: 16 x 32, B: 32 x 16, D: 16 x 16).
+//
+// Lane l = r + 16 g (r = l % 16, g = l / 16) holds
+//     A[r][8g .. 8g+7]      B[8g .. 8g+7][r]      D[4g .. 4g+3][r]
+//
+// Weights W[N, K] are the A operand and are stored in HBM as a stream of 1 KiB
+// blocks, block (tile t, step s) at index t * KS + s (KS = ceil(K / 32)); inside a
+// block lane l's 8 bf16 sit at byte 16 l.  A wave reads one block with one fully
+// coalesced 16-byte-per-lane load and feeds it to the matrix core unchanged.
+//
+// Activations X[rows, K] are the B operand.  Rows are taken in groups of 8; column
+// c < 8 of the B operand is the bf16 head of row 8 grp + c, column c + 8 its bf16
+// tail, so one matrix-core step multiplies by head and tail at once and
+// D[:, c] + D[:, c + 8] is the product with (nearly) full float32 activations.
+// Block (group grp, step s) sits at index grp * KS + s, lane layout as above.
+// ---------------------------------------------------------------------------------
+__host__ __device__ __forceinline__ size_t packed_elem_index(int row_in_tile, int k_in_step) {
+    // element offset (bf16 units) inside one 512-element block
+    int g = k_in_step >> 3, e = k_in_step & 7;
+    return (size_t)((row_in_tile + 16 * g) * 8 + e);
+}
+
+// address (bf16 units) of activation element (row, k) in a packed activation buffer
+__device__ __forceinline__ size_t xpack_index(int row, int k, int KS, int lo_half) {
+    int grp = row >> 3, c = (row & 7) + (lo_half ? 8 : 0);
+    int s = k >> 5;
+    return ((size_t)grp * KS + s) * 512 + packed_elem_index(c, k & 31);
+}
+
+struct SeqLens { int32_t len[kMaxRows]; };   // KV length of each sequence before the call
+
+}  // namespace spd

@@ -1,0 +1,78 @@
+// Host-side launch wrappers of the HIP kernels (internal to libspd).
+// Every wrapper only enqueues work on `stream` and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "common.h"
+
+namespace spd {
+
+// ---- weight re-tiling (model creation) ------------------------------------------
+enum PackMode { PACK_PLAIN = 0, PACK_CONCAT3 = 1, PACK_GATE_UP = 2 };
+// dst: packed blocks of a [N, K] matrix assembled from up to three row-major sources:
+//   PLAIN     rows of src0
+//   CONCAT3   rows of src0, then src1, then src2 (N/3 rows each)         -- fused QKV
+//   GATE_UP   tile j = 8 rows of src0 (gate) then the same 8 rows of src1 (up)
+hipError_t launch_pack_weight(const void *src0, const void *src1, const void *src2, int mode,
+                              int N, int K, void *dst, hipStream_t stream);
+size_t packed_matrix_bytes(int N, int K);
+
+// ---- skinny weight-streaming GEMM -------------------------------------------------
+enum Epilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+struct GemmTuning { int waves; int tiles_per_wg; };
+struct GemmArgs {
+    const void *W;        // packed weights [N, K]
+    const void *X;        // packed activations (B operand blocks), K columns
+    int N, K;             // logical sizes (N % 16 == 0)
+    int rows;             // valid activation rows (<= 64)
+    float *Y;             // STORE: Y[row, n] = acc ; RESIDUAL: Y[row, n] += acc   (ld = ldy)
+    int ldy;
+    void *Xout;           // SWIGLU: packed activations with K_out = N / 2 columns
+    int K_out;
+};
+hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStream_t stream);
+
+// ---- row-wise kernels -------------------------------------------------------------
+// h[row, :] = float(E[tokens[row], :]); token ids are clamped into [0, vocab)
+hipError_t launch_embed_gather(const void *embed_bf16, const int32_t *tokens, int rows, int d, int vocab,
+                               float *h, hipStream_t stream);
+// xpack <- head/tail split of RMSNorm(h[row, :]) * gain, rows <= 64, d % 32 == 0
+hipError_t launch_rmsnorm_pack(const float *h, const float *gain, int rows, int d, float eps,
+                               void *xpack, hipStream_t stream);
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t stream);
+
+// ---- attention ----------------------------------------------------------------------
+struct AttnArgs {
+    const float *qkv;        // [rows, 3 * H * dh] (q | k | v), before RoPE
+    const float *rope;       // [max_positions, dh / 2, 2] (cos, sin)
+    void *k_cache, *v_cache; // this layer: bf16 [max_seqs, H, max_positions, dh]
+    float *part_o;           // [n_seqs, H, n_split, 8, dh]
+    float *part_ml;          // [n_seqs, H, n_split, 8, 2]  (max, sum)
+    void *xout;              // packed activations, K = H * dh (attention output)
+    int n_seqs, M, H, dh, max_positions, n_split, split_len;
+    SeqLens lens;            // KV length of every sequence before this call
+};
+hipError_t launch_attention(const AttnArgs &a, hipStream_t stream);
+
+// ---- sampling ---------------------------------------------------------------------
+struct AcceptArgs {
+    const float *target, *draft;
+    const int32_t *draft_tokens;
+    const float *u;
+    int n_seqs, gamma, vocab;
+    float temperature;
+    uint32_t flags;
+    int32_t *n_accepted, *next_token;
+    float *accept_prob;      // may be NULL
+    float *stats;            // workspace: [n_seqs * (2 gamma + 1), 4]
+};
+hipError_t launch_accept(const AcceptArgs &a, hipStream_t stream);
+size_t accept_workspace_bytes(int n_seqs, int gamma);
+
+// softmax(logits[seq * ld_rows + ...]) -> probs row + one sample per sequence
+hipError_t launch_softmax_sample(const float *logits, size_t row_stride, int n_seqs, int vocab,
+                                 float temperature, const float *u, float *probs_out,
+                                 int32_t *token_out, hipStream_t stream);
+
+}  // namespace spd

@@ -1,0 +1,426 @@
+// C ABI of libspd: model object over caller-owned buffers and the orchestration of
+// one decoder forward (verify step / draft step / prefill) out of the HIP kernels.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/spd.h"
+#include "launch.h"
+
+using namespace spd;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+int32_t fail(int32_t code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return fail(SPD_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_),    \
+                        __FILE__, __LINE__);                                                   \
+    } while (0)
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+constexpr int kMinSplit = 32;      // smallest key-slice length the attention launch uses
+
+struct Layout {                    // byte offsets inside the three buffers
+    // packed
+    size_t embed, lm_head, final_norm;
+    std::vector<size_t> attn_norm, wqkv, wo, mlp_norm, wgu, wdown;
+    size_t packed_total;
+    // kv
+    size_t kv_layer_stride, kv_half, kv_total;
+    // workspace
+    size_t h, qkv, xn, xo, xf, part_o, part_ml, rope, logits, ws_total;
+    int n_split_max;
+};
+
+int32_t check_shape(const spd_model_config &c) {
+    if (c.n_layers < 1 || c.d_model < 32 || c.n_heads < 1 || c.d_ffn < 8 || c.vocab < 16 ||
+        c.max_seqs < 1 || c.max_positions < 1)
+        return fail(SPD_ERR_SHAPE, "non-positive dimension in spd_model_config");
+    if (c.d_model % 32) return fail(SPD_ERR_SHAPE, "d_model %d must be a multiple of 32", c.d_model);
+    if (c.head_dim != 64 && c.head_dim != 128)
+        return fail(SPD_ERR_SHAPE, "head_dim %d must be 64 or 128", c.head_dim);
+    if ((c.n_heads * c.head_dim) % 32)
+        return fail(SPD_ERR_SHAPE, "n_heads*head_dim must be a multiple of 32");
+    if (c.d_ffn % 8) return fail(SPD_ERR_SHAPE, "d_ffn %d must be a multiple of 8", c.d_ffn);
+    if (c.vocab % 16) return fail(SPD_ERR_SHAPE, "vocab %d must be a multiple of 16", c.vocab);
+    if (c.max_seqs > SPD_MAX_ROWS) return fail(SPD_ERR_SHAPE, "max_seqs %d exceeds %d", c.max_seqs, SPD_MAX_ROWS);
+    if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return fail(SPD_ERR_SHAPE, "bad rms_eps / rope_theta");
+    return SPD_OK;
+}
+
+void make_layout(const spd_model_config &c, Layout &L) {
+    const int d = c.d_model, HD = c.n_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    L.embed = take((size_t)V * d * 2);
+    L.lm_head = take(packed_matrix_bytes(V, d));
+    L.final_norm = take((size_t)d * 4);
+    for (int l = 0; l < c.n_layers; ++l) {
+        L.attn_norm.push_back(take((size_t)d * 4));
+        L.wqkv.push_back(take(packed_matrix_bytes(3 * HD, d)));
+        L.wo.push_back(take(packed_matrix_bytes(d, HD)));
+        L.mlp_norm.push_back(take((size_t)d * 4));
+        L.wgu.push_back(take(packed_matrix_bytes(2 * F, d)));
+        L.wdown.push_back(take(packed_matrix_bytes(d, F)));
+    }
+    L.packed_total = off;
+
+    L.kv_half = (size_t)c.max_seqs * c.n_heads * c.max_positions * c.head_dim * 2;   // K or V of a layer
+    L.kv_layer_stride = 2 * L.kv_half;
+    L.kv_total = L.kv_layer_stride * c.n_layers;
+
+    off = 0;
+    L.n_split_max = (c.max_positions + kMinSplit - 1) / kMinSplit;
+    const size_t KSd = d / 32, KShd = HD / 32, KSf = (F + 31) / 32;
+    L.h = take((size_t)kMaxRows * d * 4);
+    L.qkv = take((size_t)kMaxRows * 3 * HD * 4);
+    L.xn = take((size_t)kMaxGroups * KSd * 1024);
+    L.xo = take((size_t)kMaxGroups * KShd * 1024);
+    L.xf = take((size_t)kMaxGroups * KSf * 1024);
+    L.part_o = take((size_t)c.max_seqs * c.n_heads * L.n_split_max * 8 * c.head_dim * 4);
+    L.part_ml = take((size_t)c.max_seqs * c.n_heads * L.n_split_max * 8 * 2 * 4);
+    L.rope = take((size_t)c.max_positions * (c.head_dim / 2) * 2 * 4);
+    L.logits = take((size_t)kMaxRows * V * 4);
+    L.ws_total = off;
+}
+
+GemmTuning default_tuning(int N, int K) {
+    // Enough workgroups to cover 256 CUs a few times over, and K long enough per wave to
+    // keep several 1 KiB loads in flight: fewer tiles -> more waves splitting K.
+    int tiles = N / 16;
+    GemmTuning t;
+    t.tiles_per_wg = 1;
+    if (tiles >= 1024) t.waves = 4;
+    else if (tiles >= 512) t.waves = 8;
+    else t.waves = 16;
+    (void)K;
+    return t;
+}
+
+// SPD_TUNE="qkv:8:1,o:16:1,gu:4:2,down:16:1,lm:8:1"  (waves:tiles_per_wg), for sweeps
+void env_tuning(const char *name, GemmTuning &t) {
+    const char *env = getenv("SPD_TUNE");
+    if (!env) return;
+    std::string s(env), key = std::string(name) + ":";
+    size_t p = 0;
+    while (p < s.size()) {
+        size_t q = s.find(',', p);
+        if (q == std::string::npos) q = s.size();
+        std::string item = s.substr(p, q - p);
+        if (item.compare(0, key.size(), key) == 0) {
+            int w = 0, r = 0;
+            if (sscanf(item.c_str() + key.size(), "%d:%d", &w, &r) == 2) { t.waves = w; t.tiles_per_wg = r; }
+        }
+        p = q + 1;
+    }
+}
+
+}  // namespace
+
+struct spd_model {
+    spd_model_config cfg;
+    Layout L;
+    char *packed, *kv, *ws;
+    std::vector<int32_t> lens;
+    std::vector<float> rope_host;
+    GemmTuning t_qkv, t_o, t_gu, t_down, t_lm;
+    int attn_wg_target;
+};
+
+extern "C" {
+
+const char *spd_last_error(void) { return g_err; }
+
+int32_t spd_model_bytes(const spd_model_config *cfg, size_t *packed_bytes, size_t *kv_bytes,
+                        size_t *workspace_bytes) {
+    if (!cfg) return fail(SPD_ERR_INVALID_ARG, "NULL config");
+    int32_t rc = check_shape(*cfg);
+    if (rc) return rc;
+    Layout L;
+    make_layout(*cfg, L);
+    if (packed_bytes) *packed_bytes = L.packed_total;
+    if (kv_bytes) *kv_bytes = L.kv_total;
+    if (workspace_bytes) *workspace_bytes = L.ws_total;
+    return SPD_OK;
+}
+
+int32_t spd_model_create(const spd_model_config *cfg, const spd_weights *w, void *packed,
+                         size_t packed_bytes, void *kv_cache, size_t kv_bytes, void *workspace,
+                         size_t workspace_bytes, void *stream, spd_model **out) {
+    if (!cfg || !w || !packed || !kv_cache || !workspace || !out)
+        return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_model_create");
+    int32_t rc = check_shape(*cfg);
+    if (rc) return rc;
+    if (((uintptr_t)packed | (uintptr_t)kv_cache | (uintptr_t)workspace) & 255)
+        return fail(SPD_ERR_INVALID_ARG, "buffers must be 256-byte aligned");
+    if (!w->embed || !w->final_norm || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo ||
+        !w->mlp_norm || !w->w_gate || !w->w_up || !w->w_down || (!cfg->tied_embeddings && !w->lm_head))
+        return fail(SPD_ERR_INVALID_ARG, "NULL weight pointer");
+    spd_model *m = new (std::nothrow) spd_model;
+    if (!m) return fail(SPD_ERR_INVALID_ARG, "out of host memory");
+    m->cfg = *cfg;
+    make_layout(*cfg, m->L);
+    const Layout &L = m->L;
+    if (packed_bytes < L.packed_total || kv_bytes < L.kv_total || workspace_bytes < L.ws_total) {
+        delete m;
+        return fail(SPD_ERR_CAPACITY, "buffer smaller than spd_model_bytes reports");
+    }
+    m->packed = (char *)packed;
+    m->kv = (char *)kv_cache;
+    m->ws = (char *)workspace;
+    m->lens.assign(cfg->max_seqs, 0);
+    hipStream_t st = (hipStream_t)stream;
+    const int d = cfg->d_model, HD = cfg->n_heads * cfg->head_dim, F = cfg->d_ffn, V = cfg->vocab;
+
+#define CREATE_TRY(expr)                                                                      \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) {                                                                \
+            delete m;                                                                          \
+            return fail(SPD_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));           \
+        }                                                                                      \
+    } while (0)
+
+    CREATE_TRY(hipMemcpyAsync(m->packed + L.embed, w->embed, (size_t)V * d * 2, hipMemcpyDeviceToDevice, st));
+    CREATE_TRY(launch_pack_weight(cfg->tied_embeddings ? w->embed : w->lm_head, nullptr, nullptr, PACK_PLAIN,
+                                  V, d, m->packed + L.lm_head, st));
+    CREATE_TRY(hipMemcpyAsync(m->packed + L.final_norm, w->final_norm, (size_t)d * 4, hipMemcpyDeviceToDevice, st));
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        if (!w->attn_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->mlp_norm[l] ||
+            !w->w_gate[l] || !w->w_up[l] || !w->w_down[l]) {
+            delete m;
+            return fail(SPD_ERR_INVALID_ARG, "NULL weight pointer in layer %d", l);
+        }
+        CREATE_TRY(hipMemcpyAsync(m->packed + L.attn_norm[l], w->attn_norm[l], (size_t)d * 4, hipMemcpyDeviceToDevice, st));
+        CREATE_TRY(launch_pack_weight(w->wq[l], w->wk[l], w->wv[l], PACK_CONCAT3, 3 * HD, d, m->packed + L.wqkv[l], st));
+        CREATE_TRY(launch_pack_weight(w->wo[l], nullptr, nullptr, PACK_PLAIN, d, HD, m->packed + L.wo[l], st));
+        CREATE_TRY(hipMemcpyAsync(m->packed + L.mlp_norm[l], w->mlp_norm[l], (size_t)d * 4, hipMemcpyDeviceToDevice, st));
+        CREATE_TRY(launch_pack_weight(w->w_gate[l], w->w_up[l], nullptr, PACK_GATE_UP, 2 * F, d, m->packed + L.wgu[l], st));
+        CREATE_TRY(launch_pack_weight(w->w_down[l], nullptr, nullptr, PACK_PLAIN, d, F, m->packed + L.wdown[l], st));
+    }
+    // workspace starts cleared: the padding columns of the packed activation buffers must be zero
+    CREATE_TRY(launch_fill_zero(m->ws, L.ws_total, st));
+    // RoPE table: angle(pos, i) = pos * theta^(-2i/head_dim), computed in double
+    const int half = cfg->head_dim / 2;
+    m->rope_host.resize((size_t)cfg->max_positions * half * 2);
+    for (int p = 0; p < cfg->max_positions; ++p)
+        for (int i = 0; i < half; ++i) {
+            double ang = (double)p * std::pow((double)cfg->rope_theta, -2.0 * i / cfg->head_dim);
+            m->rope_host[((size_t)p * half + i) * 2 + 0] = (float)std::cos(ang);
+            m->rope_host[((size_t)p * half + i) * 2 + 1] = (float)std::sin(ang);
+        }
+    CREATE_TRY(hipMemcpyAsync(m->ws + L.rope, m->rope_host.data(), m->rope_host.size() * 4, hipMemcpyHostToDevice, st));
+#undef CREATE_TRY
+
+    m->t_qkv = default_tuning(3 * HD, d);   env_tuning("qkv", m->t_qkv);
+    m->t_o = default_tuning(d, HD);         env_tuning("o", m->t_o);
+    m->t_gu = default_tuning(2 * F, d);     env_tuning("gu", m->t_gu);
+    m->t_down = default_tuning(d, F);       env_tuning("down", m->t_down);
+    m->t_lm = default_tuning(V, d);         env_tuning("lm", m->t_lm);
+    m->attn_wg_target = 512;
+    if (const char *e = getenv("SPD_ATTN_WGS")) m->attn_wg_target = atoi(e) > 0 ? atoi(e) : 512;
+    *out = m;
+    return SPD_OK;
+}
+
+int32_t spd_model_destroy(spd_model *m) {
+    delete m;
+    return SPD_OK;
+}
+
+int32_t spd_kv_set_len(spd_model *m, const int32_t *len, int32_t n_seqs) {
+    if (!m || !len) return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_kv_set_len");
+    if (n_seqs < 0 || n_seqs > m->cfg.max_seqs) return fail(SPD_ERR_CAPACITY, "n_seqs %d exceeds max_seqs %d", n_seqs, m->cfg.max_seqs);
+    for (int i = 0; i < n_seqs; ++i) {
+        if (len[i] < 0) return fail(SPD_ERR_INVALID_ARG, "negative KV length");
+        if (len[i] > m->cfg.max_positions) return fail(SPD_ERR_CAPACITY, "KV length %d exceeds max_positions %d", len[i], m->cfg.max_positions);
+    }
+    for (int i = 0; i < n_seqs; ++i) m->lens[i] = len[i];
+    return SPD_OK;
+}
+
+int32_t spd_kv_get_len(const spd_model *m, int32_t *len, int32_t n_seqs) {
+    if (!m || !len) return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_kv_get_len");
+    if (n_seqs < 0 || n_seqs > m->cfg.max_seqs) return fail(SPD_ERR_CAPACITY, "n_seqs exceeds max_seqs");
+    for (int i = 0; i < n_seqs; ++i) len[i] = m->lens[i];
+    return SPD_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+// One decoder forward over M new rows for sequences seq0 .. seq0 + n_seqs - 1.
+// Input rows come from token ids (embedding gather) or from embedding rows.
+int32_t forward(spd_model *m, const int32_t *tokens, const float *embeds, int seq0, int n_seqs, int M,
+                float *logits_out, hipStream_t st) {
+    const spd_model_config &c = m->cfg;
+    const Layout &L = m->L;
+    const int rows = n_seqs * M;
+    if (M < 1 || M > SPD_MAX_M) return fail(SPD_ERR_SHAPE, "M = %d must be in 1..%d", M, SPD_MAX_M);
+    if (n_seqs < 1 || rows > SPD_MAX_ROWS) return fail(SPD_ERR_SHAPE, "n_seqs * M = %d must be in 1..%d", rows, SPD_MAX_ROWS);
+    if (seq0 < 0 || seq0 + n_seqs > c.max_seqs) return fail(SPD_ERR_CAPACITY, "sequence index beyond max_seqs %d", c.max_seqs);
+    int max_total = 0;
+    AttnArgs at;
+    for (int s = 0; s < n_seqs; ++s) {
+        int len = m->lens[seq0 + s];
+        if (len + M > c.max_positions)
+            return fail(SPD_ERR_CAPACITY, "KV cache overflow: sequence %d has %d positions, +%d > %d", seq0 + s, len, M, c.max_positions);
+        at.lens.len[s] = len;
+        if (len + M > max_total) max_total = len + M;
+    }
+    const int d = c.d_model, HD = c.n_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
+    float *h = (float *)(m->ws + L.h);
+    float *qkv = (float *)(m->ws + L.qkv);
+    void *xn = m->ws + L.xn, *xo = m->ws + L.xo, *xf = m->ws + L.xf;
+
+    if (tokens) HIP_TRY(launch_embed_gather(m->packed + L.embed, tokens, rows, d, V, h, st));
+    else HIP_TRY(hipMemcpyAsync(h, embeds, (size_t)rows * d * 4, hipMemcpyDeviceToDevice, st));
+
+    // key-range split: aim at ~attn_wg_target workgroups, slices of 32..256 keys
+    int want_split = m->attn_wg_target / (n_seqs * c.n_heads);
+    if (want_split < 1) want_split = 1;
+    int split_len = (max_total + want_split - 1) / want_split;
+    split_len = (split_len + 31) / 32 * 32;
+    if (split_len < kMinSplit) split_len = kMinSplit;
+    if (split_len > 256) split_len = 256;
+    at.n_split = (max_total + split_len - 1) / split_len;
+    at.split_len = split_len;
+    at.qkv = qkv;
+    at.rope = (const float *)(m->ws + L.rope);
+    at.part_o = (float *)(m->ws + L.part_o);
+    at.part_ml = (float *)(m->ws + L.part_ml);
+    at.xout = xo;
+    at.n_seqs = n_seqs; at.M = M; at.H = c.n_heads; at.dh = c.head_dim; at.max_positions = c.max_positions;
+
+    for (int l = 0; l < c.n_layers; ++l) {
+        HIP_TRY(launch_rmsnorm_pack(h, (const float *)(m->packed + L.attn_norm[l]), rows, d, c.rms_eps, xn, st));
+        GemmArgs g{};
+        g.W = m->packed + L.wqkv[l]; g.X = xn; g.N = 3 * HD; g.K = d; g.rows = rows; g.Y = qkv; g.ldy = 3 * HD;
+        HIP_TRY(launch_gemm(g, EPI_STORE, m->t_qkv, st));
+        char *kv_l = m->kv + (size_t)l * L.kv_layer_stride + (size_t)seq0 * c.n_heads * c.max_positions * c.head_dim * 2;
+        at.k_cache = kv_l;
+        at.v_cache = kv_l + L.kv_half;
+        HIP_TRY(launch_attention(at, st));
+        g = GemmArgs{};
+        g.W = m->packed + L.wo[l]; g.X = xo; g.N = d; g.K = HD; g.rows = rows; g.Y = h; g.ldy = d;
+        HIP_TRY(launch_gemm(g, EPI_RESIDUAL, m->t_o, st));
+        HIP_TRY(launch_rmsnorm_pack(h, (const float *)(m->packed + L.mlp_norm[l]), rows, d, c.rms_eps, xn, st));
+        g = GemmArgs{};
+        g.W = m->packed + L.wgu[l]; g.X = xn; g.N = 2 * F; g.K = d; g.rows = rows; g.Xout = xf; g.K_out = F;
+        HIP_TRY(launch_gemm(g, EPI_SWIGLU, m->t_gu, st));
+        g = GemmArgs{};
+        g.W = m->packed + L.wdown[l]; g.X = xf; g.N = d; g.K = F; g.rows = rows; g.Y = h; g.ldy = d;
+        HIP_TRY(launch_gemm(g, EPI_RESIDUAL, m->t_down, st));
+    }
+    if (logits_out) {
+        HIP_TRY(launch_rmsnorm_pack(h, (const float *)(m->packed + L.final_norm), rows, d, c.rms_eps, xn, st));
+        GemmArgs g{};
+        g.W = m->packed + L.lm_head; g.X = xn; g.N = V; g.K = d; g.rows = rows; g.Y = logits_out; g.ldy = V;
+        HIP_TRY(launch_gemm(g, EPI_STORE, m->t_lm, st));
+    }
+    for (int s = 0; s < n_seqs; ++s) m->lens[seq0 + s] += M;
+    return SPD_OK;
+}
+
+int32_t prefill_common(spd_model *m, int32_t seq, const float *embeds, const int32_t *tokens, int32_t n_rows,
+                       float *last_logits, hipStream_t st) {
+    if (!m || (!embeds && !tokens)) return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_prefill");
+    if (n_rows < 1) return fail(SPD_ERR_INVALID_ARG, "n_rows must be positive");
+    if (seq < 0 || seq >= m->cfg.max_seqs) return fail(SPD_ERR_CAPACITY, "sequence index %d beyond max_seqs %d", seq, m->cfg.max_seqs);
+    if (m->lens[seq] + n_rows > m->cfg.max_positions)
+        return fail(SPD_ERR_CAPACITY, "KV cache overflow in prefill: %d + %d > %d", m->lens[seq], n_rows, m->cfg.max_positions);
+    float *scratch = (float *)(m->ws + m->L.logits);
+    for (int r0 = 0; r0 < n_rows; r0 += SPD_MAX_M) {
+        int M = n_rows - r0 < SPD_MAX_M ? n_rows - r0 : SPD_MAX_M;
+        bool last = r0 + M >= n_rows;
+        int32_t rc = forward(m, tokens ? tokens + r0 : nullptr, embeds ? embeds + (size_t)r0 * m->cfg.d_model : nullptr,
+                             seq, 1, M, (last && last_logits) ? scratch : nullptr, st);
+        if (rc) return rc;
+        if (last && last_logits)
+            HIP_TRY(hipMemcpyAsync(last_logits, scratch + (size_t)(M - 1) * m->cfg.vocab, (size_t)m->cfg.vocab * 4,
+                                   hipMemcpyDeviceToDevice, st));
+    }
+    return SPD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t spd_prefill(spd_model *m, int32_t seq, const float *embeds, int32_t n_rows, float *last_logits, void *stream) {
+    if (!embeds) return fail(SPD_ERR_INVALID_ARG, "NULL embeds");
+    return prefill_common(m, seq, embeds, nullptr, n_rows, last_logits, (hipStream_t)stream);
+}
+
+int32_t spd_prefill_tokens(spd_model *m, int32_t seq, const int32_t *tokens, int32_t n_rows, float *last_logits, void *stream) {
+    if (!tokens) return fail(SPD_ERR_INVALID_ARG, "NULL tokens");
+    return prefill_common(m, seq, nullptr, tokens, n_rows, last_logits, (hipStream_t)stream);
+}
+
+int32_t spd_verify_forward(spd_model *m, const int32_t *tokens, int32_t n_seqs, int32_t M, float *logits_out, void *stream) {
+    if (!m || !tokens || !logits_out) return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_verify_forward");
+    return forward(m, tokens, nullptr, 0, n_seqs, M, logits_out, (hipStream_t)stream);
+}
+
+int32_t spd_draft_step(spd_model *m, const int32_t *tokens_in, int32_t n_seqs, int32_t n_in, float temperature,
+                       const float *u_draft, float *D_row_out, int32_t *token_out, void *stream) {
+    if (!m || !tokens_in || !u_draft || !D_row_out || !token_out) return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_draft_step");
+    if (n_in < 1 || n_in > 2) return fail(SPD_ERR_SHAPE, "n_in = %d must be 1 or 2", n_in);
+    if (!(temperature >= 0.f)) return fail(SPD_ERR_INVALID_ARG, "temperature must be >= 0");
+    float *scratch = (float *)(m->ws + m->L.logits);
+    int32_t rc = forward(m, tokens_in, nullptr, 0, n_seqs, n_in, scratch, (hipStream_t)stream);
+    if (rc) return rc;
+    const size_t V = m->cfg.vocab;
+    HIP_TRY(launch_softmax_sample(scratch + (size_t)(n_in - 1) * V, (size_t)n_in * V, n_seqs, (int)V, temperature,
+                                  u_draft, D_row_out, token_out, (hipStream_t)stream));
+    return SPD_OK;
+}
+
+int32_t spd_accept_workspace_bytes(int32_t n_seqs, int32_t gamma, int32_t vocab, size_t *bytes) {
+    if (!bytes || n_seqs < 1 || gamma < 1 || vocab < 1) return fail(SPD_ERR_INVALID_ARG, "bad argument to spd_accept_workspace_bytes");
+    *bytes = accept_workspace_bytes(n_seqs, gamma);
+    return SPD_OK;
+}
+
+int32_t spd_speculative_accept(const float *target, const float *draft, const int32_t *draft_tokens, const float *u,
+                               int32_t n_seqs, int32_t gamma, int32_t vocab, float temperature, uint32_t flags,
+                               int32_t *n_accepted_out, int32_t *next_token_out, float *accept_prob_out,
+                               void *workspace, size_t workspace_bytes, void *stream) {
+    if (!target || !draft || !draft_tokens || !u || !n_accepted_out || !next_token_out || !workspace)
+        return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_speculative_accept");
+    if (n_seqs < 1 || gamma < 1 || gamma > 63 || vocab < 1) return fail(SPD_ERR_INVALID_ARG, "n_seqs, vocab >= 1 and 1 <= gamma <= 63 required");
+    if (!(temperature >= 0.f)) return fail(SPD_ERR_INVALID_ARG, "temperature must be >= 0");
+    if (flags & ~3u) return fail(SPD_ERR_INVALID_ARG, "unknown flag bits");
+    if (workspace_bytes < accept_workspace_bytes(n_seqs, gamma)) return fail(SPD_ERR_CAPACITY, "accept workspace too small");
+    AcceptArgs a;
+    a.target = target; a.draft = draft; a.draft_tokens = draft_tokens; a.u = u;
+    a.n_seqs = n_seqs; a.gamma = gamma; a.vocab = vocab; a.temperature = temperature; a.flags = flags;
+    a.n_accepted = n_accepted_out; a.next_token = next_token_out; a.accept_prob = accept_prob_out;
+    a.stats = (float *)workspace;
+    HIP_TRY(launch_accept(a, (hipStream_t)stream));
+    return SPD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,262 @@
+// Speculative sampling on the device: softmax statistics of logit rows, the accept
+// test u * D(d) < T(d), the residual max(0, T - D) and the fixed-point inverse-CDF
+// sampler that draws the replacement / bonus token (and the draft's own samples).
+//
+// Fixed-point sampler: w(x) = floor(r(x) * 2^32) as 64-bit integers, S = sum w (integer,
+// so independent of the reduction tree), threshold = floor(k_u * S / 2^24) with
+// k_u = u * 2^24, result = first x whose inclusive running sum exceeds the threshold.
+// Every decision after the float32 probabilities is integer arithmetic, which is what
+// makes the result reproducible bit for bit by any other implementation.
+#include "launch.h"
+
+namespace spd {
+
+constexpr int kSampThreads = 1024;
+
+struct RowStats { float mx; float sum; int argmax; int pad; };
+
+__device__ __forceinline__ unsigned long long shfl_up_u64(unsigned long long v, int off) {
+    unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
+    lo = __shfl_up(lo, off);
+    hi = __shfl_up(hi, off);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// Exclusive prefix sum of one value per thread over the whole workgroup (1024 threads);
+// *total receives the workgroup sum.  `tmp` = 17 x u64 of shared memory.
+__device__ unsigned long long block_exclusive_scan(unsigned long long v, unsigned long long *tmp,
+                                                   unsigned long long *total) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    unsigned long long incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        unsigned long long t = shfl_up_u64(incl, off);
+        if (lane >= off) incl += t;
+    }
+    __syncthreads();                      // tmp may still be in use by a previous call
+    if (lane == 63) tmp[w] = incl;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long run = 0;
+        for (int i = 0; i < kSampThreads / 64; ++i) { unsigned long long t = tmp[i]; tmp[i] = run; run += t; }
+        tmp[16] = run;
+    }
+    __syncthreads();
+    *total = tmp[16];
+    return tmp[w] + incl - v;
+}
+
+__device__ __forceinline__ unsigned long long fixed_weight(float r) {
+    return (unsigned long long)(r * 4294967296.0f);          // exact scale, truncation
+}
+
+__device__ __forceinline__ unsigned long long threshold_of(float u, unsigned long long S) {
+    unsigned long long k_u = (unsigned long long)(u * 16777216.0f);   // u is a multiple of 2^-24
+    unsigned long long hi = __umul64hi(k_u, S), lo = k_u * S;
+    return (hi << 40) | (lo >> 24);                           // floor(k_u * S / 2^24), 128-bit product
+}
+
+// Draw from the distribution proportional to r(x), x in [0, V).  Returns -1 if every
+// weight truncates to zero.  All threads of the workgroup must call it; all get the result.
+template <class F>
+__device__ int sample_inverse_cdf(F r, int V, float u, unsigned long long *tmp, int *result) {
+    const int C = (V + kSampThreads - 1) / kSampThreads;
+    const int x0 = min(V, (int)threadIdx.x * C), x1 = min(V, x0 + C);
+    unsigned long long part = 0;
+    for (int x = x0; x < x1; ++x) part += fixed_weight(r(x));
+    unsigned long long S;
+    unsigned long long excl = block_exclusive_scan(part, tmp, &S);
+    if (threadIdx.x == 0) *result = -1;
+    __syncthreads();
+    if (S != 0) {
+        unsigned long long thr = threshold_of(u, S);
+        if (excl <= thr && thr < excl + part) {               // exactly one thread
+            unsigned long long run = excl;
+            for (int x = x0; x < x1; ++x) {
+                run += fixed_weight(r(x));
+                if (run > thr) { *result = x; break; }
+            }
+        }
+    }
+    __syncthreads();
+    return *result;
+}
+
+// ---------------------------------------------------------------------------------
+// softmax statistics of logit rows: max, argmax (lowest index), sum exp((l - max) / temp)
+// ---------------------------------------------------------------------------------
+__device__ void row_stats(const float *__restrict__ row, int V, float inv_temp, RowStats *out_shared) {
+    // out_shared: one RowStats in shared memory, valid after the call for all threads
+    __shared__ float s_mx[kSampThreads / 64];
+    __shared__ int s_arg[kSampThreads / 64];
+    __shared__ float s_sum[kSampThreads / 64];
+    float mx = -INFINITY;
+    int arg = 0x7fffffff;
+    for (int x = threadIdx.x; x < V; x += blockDim.x) {
+        float v = row[x];
+        if (v > mx) { mx = v; arg = x; }                       // strided: first hit is the lowest index
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        float om = __shfl_xor(mx, off);
+        int oa = __shfl_xor(arg, off);
+        if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
+    }
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    if (lane == 0) { s_mx[w] = mx; s_arg[w] = arg; }
+    __syncthreads();
+    mx = s_mx[0]; arg = s_arg[0];
+    for (int i = 1; i < nw; ++i)
+        if (s_mx[i] > mx || (s_mx[i] == mx && s_arg[i] < arg)) { mx = s_mx[i]; arg = s_arg[i]; }
+    float sum = 0.f;
+    for (int x = threadIdx.x; x < V; x += blockDim.x) sum += expf((row[x] - mx) * inv_temp);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    if (lane == 0) s_sum[w] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+        for (int i = 0; i < nw; ++i) t += s_sum[i];
+        out_shared->mx = mx; out_shared->sum = t; out_shared->argmax = arg; out_shared->pad = 0;
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(kSampThreads) void accept_stats_kernel(AcceptArgs a) {
+    // one workgroup per logits row: target rows first, then draft rows
+    const int n_t = a.n_seqs * (a.gamma + 1);
+    const int r = blockIdx.x;
+    const bool is_t = r < n_t;
+    if (is_t && (a.flags & 1u)) return;
+    if (!is_t && (a.flags & 2u)) return;
+    const float *row = is_t ? a.target + (size_t)r * a.vocab : a.draft + (size_t)(r - n_t) * a.vocab;
+    const float inv_temp = a.temperature > 0.f ? 1.0f / a.temperature : 1.0f;
+    __shared__ RowStats st;
+    row_stats(row, a.vocab, inv_temp, &st);
+    if (threadIdx.x == 0) reinterpret_cast<RowStats *>(a.stats)[r] = st;
+}
+
+// probability of token x in a row given its statistics (or the row itself if it holds probabilities)
+struct RowProb {
+    const float *row;
+    RowStats st;
+    float inv_temp;
+    int mode;           // 0 probabilities, 1 softmax of logits, 2 greedy one-hot
+    __device__ __forceinline__ float operator()(int x) const {
+        if (mode == 0) return row[x];
+        if (mode == 2) return x == st.argmax ? 1.0f : 0.0f;
+        return expf((row[x] - st.mx) * inv_temp) / st.sum;
+    }
+};
+
+__global__ __launch_bounds__(kSampThreads) void accept_decide_kernel(AcceptArgs a) {
+    const int seq = blockIdx.x, G = a.gamma, V = a.vocab;
+    const int n_t = a.n_seqs * (G + 1);
+    const RowStats *stats = reinterpret_cast<const RowStats *>(a.stats);
+    const float inv_temp = a.temperature > 0.f ? 1.0f / a.temperature : 1.0f;
+    const int t_mode = (a.flags & 1u) ? 0 : (a.temperature > 0.f ? 1 : 2);
+    const int d_mode = (a.flags & 2u) ? 0 : (a.temperature > 0.f ? 1 : 2);
+    __shared__ int s_acc[64];
+    __shared__ int s_k;
+    __shared__ unsigned long long tmp[17];
+    __shared__ int result;
+
+    auto t_row = [&](int j) {
+        RowProb p;
+        p.row = a.target + ((size_t)seq * (G + 1) + j) * V;
+        p.st = t_mode == 0 ? RowStats{0.f, 1.f, 0, 0} : stats[seq * (G + 1) + j];
+        p.inv_temp = inv_temp; p.mode = t_mode;
+        return p;
+    };
+    auto d_row = [&](int j) {
+        RowProb p;
+        p.row = a.draft + ((size_t)seq * G + j) * V;
+        p.st = d_mode == 0 ? RowStats{0.f, 1.f, 0, 0} : stats[n_t + seq * G + j];
+        p.inv_temp = inv_temp; p.mode = d_mode;
+        return p;
+    };
+
+    // accept tests: u_j * D_j(d_j) < T_j(d_j), one float32 multiply and one compare
+    if ((int)threadIdx.x < G) {
+        int j = threadIdx.x;
+        int d = min(max(a.draft_tokens[seq * G + j], 0), V - 1);   // never index outside the row
+        float Tx = t_row(j)(d), Dx = d_row(j)(d);
+        float u = a.u[seq * (G + 1) + j];
+        s_acc[j] = (__fmul_rn(u, Dx) < Tx) ? 1 : 0;
+        if (a.accept_prob) {
+            float ap = (Dx == 0.f) ? (Tx > 0.f ? 1.0f : 0.0f) : fminf(1.0f, Tx / Dx);
+            a.accept_prob[seq * G + j] = ap;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int k = 0;
+        while (k < G && s_acc[k]) ++k;
+        s_k = k;
+    }
+    __syncthreads();
+    const int k = s_k;
+
+    int y;
+    if (k < G) {
+        RowProb T = t_row(k), D = d_row(k);
+        y = sample_inverse_cdf([&](int x) { return fmaxf(0.0f, __fsub_rn(T(x), D(x))); }, V,
+                               a.u[seq * (G + 1) + G], tmp, &result);
+        if (y < 0) y = sample_inverse_cdf(T, V, a.u[seq * (G + 1) + G], tmp, &result);
+    } else {
+        y = sample_inverse_cdf(t_row(G), V, a.u[seq * (G + 1) + G], tmp, &result);
+    }
+    if (threadIdx.x == 0) {
+        a.n_accepted[seq] = k;
+        a.next_token[seq] = y < 0 ? 0 : y;
+    }
+}
+
+size_t accept_workspace_bytes(int n_seqs, int gamma) {
+    return (size_t)n_seqs * (2 * gamma + 1) * sizeof(RowStats);
+}
+
+hipError_t launch_accept(const AcceptArgs &a, hipStream_t stream) {
+    if (a.gamma < 1 || a.gamma > 63) return hipErrorInvalidValue;
+    const bool need_stats = ((a.flags & 3u) != 3u);
+    if (need_stats) {
+        int n_rows = a.n_seqs * (2 * a.gamma + 1);
+        hipLaunchKernelGGL(accept_stats_kernel, dim3(n_rows), dim3(kSampThreads), 0, stream, a);
+    }
+    hipLaunchKernelGGL(accept_decide_kernel, dim3(a.n_seqs), dim3(kSampThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// draft step tail: D row = softmax(logits / temp) written out, one token drawn from it
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSampThreads) void softmax_sample_kernel(const float *__restrict__ logits,
+                                                                       size_t row_stride, int V,
+                                                                       float temperature,
+                                                                       const float *__restrict__ u,
+                                                                       float *__restrict__ probs_out,
+                                                                       int32_t *__restrict__ token_out) {
+    const int seq = blockIdx.x;
+    const float *row = logits + (size_t)seq * row_stride;
+    float *out = probs_out + (size_t)seq * V;
+    __shared__ RowStats st;
+    __shared__ unsigned long long tmp[17];
+    __shared__ int result;
+    const float inv_temp = temperature > 0.f ? 1.0f / temperature : 1.0f;
+    row_stats(row, V, inv_temp, &st);
+    RowProb p;
+    p.row = row; p.st = st; p.inv_temp = inv_temp; p.mode = temperature > 0.f ? 1 : 2;
+    for (int x = threadIdx.x; x < V; x += blockDim.x) out[x] = p(x);
+    int y = sample_inverse_cdf(p, V, u[seq], tmp, &result);
+    if (threadIdx.x == 0) token_out[seq] = y < 0 ? 0 : y;
+}
+
+hipError_t launch_softmax_sample(const float *logits, size_t row_stride, int n_seqs, int vocab,
+                                 float temperature, const float *u, float *probs_out,
+                                 int32_t *token_out, hipStream_t stream) {
+    hipLaunchKernelGGL(softmax_sample_kernel, dim3(n_seqs), dim3(kSampThreads), 0, stream, logits,
+                       row_stride, vocab, temperature, u, probs_out, token_out);
+    return hipGetLastError();
+}
+
+}  // namespace spd

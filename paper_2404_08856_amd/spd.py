@@ -1,0 +1,196 @@
+"""ctypes binding of libspd (argument marshalling only; every step runs in the HIP kernels).
+
+Function names and arguments mirror include/spd.h.  torch is used for device memory
+and the current stream, nothing else.  There is no fallback: if the shared library
+has not been built, importing this module raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspd.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2404_08856_amd.build, "
+                      "or __graft_entry__.build()); there is no CPU fallback")
+_lib = ctypes.CDLL(LIB_PATH)
+
+SPD_OK = 0
+SPD_ERR_INVALID_ARG, SPD_ERR_SHAPE, SPD_ERR_CAPACITY, SPD_ERR_HIP = -1, -2, -3, -4
+SPD_TARGET_IS_PROBS, SPD_DRAFT_IS_PROBS = 1, 2
+SPD_MAX_ROWS, SPD_MAX_M = 64, 8
+
+EXPORTS = ["spd_last_error", "spd_model_bytes", "spd_model_create", "spd_model_destroy", "spd_kv_set_len",
+           "spd_kv_get_len", "spd_prefill", "spd_prefill_tokens", "spd_verify_forward", "spd_draft_step",
+           "spd_accept_workspace_bytes", "spd_speculative_accept"]
+
+
+class SpdError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libspd error {code}: {msg}")
+        self.code = code
+
+
+class spd_model_config(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int32), ("d_model", ctypes.c_int32), ("n_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("d_ffn", ctypes.c_int32), ("vocab", ctypes.c_int32),
+                ("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float),
+                ("tied_embeddings", ctypes.c_int32), ("max_seqs", ctypes.c_int32),
+                ("max_positions", ctypes.c_int32)]
+
+
+_PP = ctypes.POINTER(ctypes.c_void_p)
+
+
+class spd_weights(ctypes.Structure):
+    _fields_ = [("embed", ctypes.c_void_p), ("lm_head", ctypes.c_void_p), ("final_norm", ctypes.c_void_p),
+                ("attn_norm", _PP), ("wq", _PP), ("wk", _PP), ("wv", _PP), ("wo", _PP),
+                ("mlp_norm", _PP), ("w_gate", _PP), ("w_up", _PP), ("w_down", _PP)]
+
+
+_vp, _i32, _f32, _u32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_uint32, ctypes.c_size_t
+_szp = ctypes.POINTER(ctypes.c_size_t)
+_lib.spd_last_error.restype = ctypes.c_char_p
+_lib.spd_last_error.argtypes = []
+_lib.spd_model_bytes.argtypes = [ctypes.POINTER(spd_model_config), _szp, _szp, _szp]
+_lib.spd_model_create.argtypes = [ctypes.POINTER(spd_model_config), ctypes.POINTER(spd_weights), _vp, _sz, _vp, _sz,
+                                  _vp, _sz, _vp, ctypes.POINTER(_vp)]
+_lib.spd_model_destroy.argtypes = [_vp]
+_lib.spd_kv_set_len.argtypes = [_vp, ctypes.POINTER(_i32), _i32]
+_lib.spd_kv_get_len.argtypes = [_vp, ctypes.POINTER(_i32), _i32]
+_lib.spd_prefill.argtypes = [_vp, _i32, _vp, _i32, _vp, _vp]
+_lib.spd_prefill_tokens.argtypes = [_vp, _i32, _vp, _i32, _vp, _vp]
+_lib.spd_verify_forward.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp]
+_lib.spd_draft_step.argtypes = [_vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp, _vp]
+_lib.spd_accept_workspace_bytes.argtypes = [_i32, _i32, _i32, _szp]
+_lib.spd_speculative_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _u32, _vp, _vp, _vp, _vp, _sz, _vp]
+for _name in EXPORTS:
+    if _name != "spd_last_error":
+        getattr(_lib, _name).restype = _i32
+
+
+def spd_last_error():
+    return _lib.spd_last_error().decode()
+
+
+def _check(rc):
+    if rc != SPD_OK:
+        raise SpdError(rc, spd_last_error())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device, contiguous tensors only"
+    if dtype is not None:
+        assert t.dtype == dtype, f"expected {dtype}, got {t.dtype}"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def make_config(shape, max_seqs, max_positions):
+    """spd_model_config from a synth.ModelShape-like object."""
+    return spd_model_config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn,
+                            shape.vocab, shape.rms_eps, shape.rope_theta, int(shape.tied_embeddings),
+                            max_seqs, max_positions)
+
+
+def spd_model_bytes(cfg):
+    p, k, w = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(_lib.spd_model_bytes(ctypes.byref(cfg), ctypes.byref(p), ctypes.byref(k), ctypes.byref(w)))
+    return p.value, k.value, w.value
+
+
+class Model:
+    """Owns the three device buffers (torch allocations) and the spd_model handle."""
+
+    def __init__(self, cfg, weights, device="cuda"):
+        """weights: dict as produced by synth.make_weights, tensors on `device`."""
+        self.cfg = cfg
+        pb, kb, wb = spd_model_bytes(cfg)
+        self.packed = torch.empty(pb, dtype=torch.uint8, device=device)
+        self.kv = torch.zeros(kb, dtype=torch.uint8, device=device)
+        self.workspace = torch.empty(wb, dtype=torch.uint8, device=device)
+        L = cfg.n_layers
+        assert len(weights["layers"]) == L
+
+        def arr(key, dtype):
+            a = (ctypes.c_void_p * L)()
+            for l, lw in enumerate(weights["layers"]):
+                a[l] = _ptr(lw[key], dtype).value
+            return a
+
+        bf, f32 = torch.bfloat16, torch.float32
+        keep = [arr("attn_norm", f32), arr("wq", bf), arr("wk", bf), arr("wv", bf), arr("wo", bf),
+                arr("mlp_norm", f32), arr("w_gate", bf), arr("w_up", bf), arr("w_down", bf)]
+        w = spd_weights(_ptr(weights["embed"], bf), _ptr(weights.get("lm_head"), bf), _ptr(weights["final_norm"], f32),
+                        *[ctypes.cast(a, _PP) for a in keep])
+        handle = ctypes.c_void_p()
+        _check(_lib.spd_model_create(ctypes.byref(cfg), ctypes.byref(w), _ptr(self.packed), pb, _ptr(self.kv), kb,
+                                     _ptr(self.workspace), wb, _stream(), ctypes.byref(handle)))
+        self.handle = handle
+        torch.cuda.current_stream().synchronize()     # re-tiling done: the caller may drop `weights`
+
+    def close(self):
+        if getattr(self, "handle", None):
+            _lib.spd_model_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        self.close()
+
+    # --- thin wrappers, same names as the C entry points ---------------------------------
+    def spd_kv_set_len(self, lens):
+        a = (ctypes.c_int32 * len(lens))(*[int(x) for x in lens])
+        _check(_lib.spd_kv_set_len(self.handle, a, len(lens)))
+
+    def spd_kv_get_len(self, n_seqs):
+        a = (ctypes.c_int32 * n_seqs)()
+        _check(_lib.spd_kv_get_len(self.handle, a, n_seqs))
+        return list(a)
+
+    def spd_prefill(self, seq, embeds, last_logits=None):
+        _check(_lib.spd_prefill(self.handle, seq, _ptr(embeds, torch.float32), embeds.shape[0],
+                                _ptr(last_logits, torch.float32), _stream()))
+
+    def spd_prefill_tokens(self, seq, tokens, last_logits=None):
+        _check(_lib.spd_prefill_tokens(self.handle, seq, _ptr(tokens, torch.int32), tokens.shape[0],
+                                       _ptr(last_logits, torch.float32), _stream()))
+
+    def spd_verify_forward(self, tokens, logits_out):
+        n_seqs, M = tokens.shape
+        assert logits_out.shape == (n_seqs, M, self.cfg.vocab)
+        _check(_lib.spd_verify_forward(self.handle, _ptr(tokens, torch.int32), n_seqs, M,
+                                       _ptr(logits_out, torch.float32), _stream()))
+
+    def spd_draft_step(self, tokens_in, temperature, u_draft, D_row_out, token_out):
+        n_seqs, n_in = tokens_in.shape
+        assert D_row_out.shape == (n_seqs, self.cfg.vocab) and token_out.shape == (n_seqs,) and u_draft.shape == (n_seqs,)
+        _check(_lib.spd_draft_step(self.handle, _ptr(tokens_in, torch.int32), n_seqs, n_in, float(temperature),
+                                   _ptr(u_draft, torch.float32), _ptr(D_row_out, torch.float32),
+                                   _ptr(token_out, torch.int32), _stream()))
+
+
+def spd_accept_workspace_bytes(n_seqs, gamma, vocab):
+    b = ctypes.c_size_t()
+    _check(_lib.spd_accept_workspace_bytes(n_seqs, gamma, vocab, ctypes.byref(b)))
+    return b.value
+
+
+def spd_speculative_accept(target, draft, draft_tokens, u, temperature, flags, n_accepted_out, next_token_out,
+                           accept_prob_out=None, workspace=None):
+    n_seqs, g1, vocab = target.shape
+    gamma = g1 - 1
+    assert draft.shape == (n_seqs, gamma, vocab) and draft_tokens.shape == (n_seqs, gamma) and u.shape == (n_seqs, g1)
+    if workspace is None:
+        workspace = torch.empty(spd_accept_workspace_bytes(n_seqs, gamma, vocab), dtype=torch.uint8, device=target.device)
+    _check(_lib.spd_speculative_accept(_ptr(target, torch.float32), _ptr(draft, torch.float32),
+                                       _ptr(draft_tokens, torch.int32), _ptr(u, torch.float32), n_seqs, gamma, vocab,
+                                       float(temperature), int(flags), _ptr(n_accepted_out, torch.int32),
+                                       _ptr(next_token_out, torch.int32), _ptr(accept_prob_out, torch.float32),
+                                       _ptr(workspace), workspace.numel(), _stream()))

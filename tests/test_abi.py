@@ -1,0 +1,59 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header
+declares, and its host-only entry points validate their arguments (no GPU work)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "spd.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2404_08856_amd import spd
+    lib = ctypes.CDLL(spd.LIB_PATH)
+    names = declared_functions()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in spd.h but not exported"
+    assert sorted(spd.EXPORTS) == names
+
+
+def test_model_bytes_and_shape_validation():
+    from paper_2404_08856_amd import spd, synth
+    s = synth.SHAPES["llama7b"]
+    cfg = spd.make_config(s, max_seqs=1, max_positions=1024)
+    packed, kv, ws = spd.spd_model_bytes(cfg)
+    # packed = bf16 matrices (same byte count as row-major: all dims divide the tile) + embed + gains
+    assert packed >= s.streamed_weight_bytes() + s.vocab * s.d_model * 2
+    assert packed < 1.01 * (s.streamed_weight_bytes() + s.vocab * s.d_model * 2)
+    assert kv == s.n_layers * 2 * 1 * s.n_heads * 1024 * s.head_dim * 2
+    assert ws > 0
+    bad = spd.make_config(s, 1, 1024)
+    bad.head_dim = 96
+    with pytest.raises(spd.SpdError) as e:
+        spd.spd_model_bytes(bad)
+    assert e.value.code == spd.SPD_ERR_SHAPE and "head_dim" in str(e.value)
+    bad = spd.make_config(s, 1, 1024)
+    bad.d_model = 4100
+    with pytest.raises(spd.SpdError):
+        spd.spd_model_bytes(bad)
+    # K not a multiple of 32 is padded per 16-row tile (tiny config: d_ffn = 688)
+    t = synth.SHAPES["tiny_target"]
+    p2, _, _ = spd.spd_model_bytes(spd.make_config(t, 1, 128))
+    assert p2 > t.streamed_weight_bytes()
+
+
+def test_accept_workspace_bytes_and_argument_checks():
+    from paper_2404_08856_amd import spd
+    assert spd.spd_accept_workspace_bytes(64, 4, 32000) == 64 * 9 * 16
+    with pytest.raises(spd.SpdError) as e:
+        spd.spd_accept_workspace_bytes(0, 4, 32000)
+    assert e.value.code == spd.SPD_ERR_INVALID_ARG

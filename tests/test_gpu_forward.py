@@ -1,0 +1,185 @@
+"""GPU parity of the decoder forward (verify step, draft step, prefill) against the oracle.
+
+Every case feeds the same seeded inputs to the HIP library (through the C ABI) and to
+the CPU oracle and compares logits element by element with the benchmark spec's tolerance
+(max-abs 3e-2, mean-abs 3e-3: bf16 weights, float32 accumulation)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import decoder as dec
+from paper_2404_08856_amd import synth
+from tests.helpers import check_logits, oracle_cfg, randomize_gains, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def spd_mod():
+    from paper_2404_08856_amd import spd
+    return spd
+
+
+def build_pair(shape, seed, max_seqs, max_positions, gains=True):
+    spd = spd_mod()
+    w = synth.make_weights(shape, seed)
+    if gains:
+        randomize_gains(w)
+    model = spd.Model(spd.make_config(shape, max_seqs, max_positions), to_device(w))
+    return model, synth.weights_to_numpy(w)
+
+
+def run_case(shape, m_img, n_text, M, seed=0, extra_steps=0):
+    """prefill [image rows ; text] then verify M tokens; returns error stats."""
+    print(f"case shape={shape} m_img={m_img} n_text={n_text} M={M} seed={seed}", flush=True)
+    cap = m_img + n_text + M * (1 + extra_steps) + 8
+    model, wn = build_pair(shape, seed, 1, cap)
+    cfg = oracle_cfg(shape)
+    toks = synth.text_tokens(n_text, shape.vocab, seed)
+    x_text = dec.embed_tokens(wn, toks)
+    if m_img:
+        img = synth.image_rows(m_img, shape.d_model, seed)
+        x = np.concatenate([img.astype(np.float64), x_text])
+    else:
+        x = x_text
+    cache = dec.KVCache(cfg, cap)
+    ref_prefill = dec.forward_rows(cfg, wn, cache, x)
+    last = torch.empty(shape.vocab, dtype=torch.float32, device="cuda")
+    model.spd_prefill(0, torch.from_numpy(x.astype(np.float32)).cuda(), last)
+    check_logits(last.cpu().numpy(), ref_prefill[-1], "prefill last row")
+    stats = None
+    for step in range(1 + extra_steps):
+        vt = synth.text_tokens(M, shape.vocab, seed + 100 + step)
+        ref = dec.forward_tokens(cfg, wn, cache, vt)
+        out = torch.empty((1, M, shape.vocab), dtype=torch.float32, device="cuda")
+        model.spd_verify_forward(torch.from_numpy(vt).cuda()[None].contiguous(), out)
+        stats = check_logits(out.cpu().numpy()[0], ref, f"verify step {step}")
+    assert model.spd_kv_get_len(1) == [cache.length]
+    model.close()
+    return stats
+
+
+def test_tiny_target_prefill_and_verify():
+    # 32 image rows + 32 text tokens, gamma + 1 = 5 (the tiny correctness configuration)
+    mx, mean = run_case(synth.SHAPES["tiny_target"], 32, 32, 5)
+    print("tiny verify err", mx, mean)
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 6, 7, 8])
+def test_tiny_all_row_counts(M):
+    run_case(synth.SHAPES["tiny_target"], 5, 6, M, seed=M)
+
+
+@pytest.mark.parametrize("prefix", [1, 7, 8, 9, 27, 31, 32, 33, 63, 64, 65, 255, 256, 257, 300])
+def test_tiny_prefix_lengths_across_chunk_and_split_boundaries(prefix):
+    # text-only prefixes whose lengths straddle the 8-row prefill chunk and the key-slice sizes
+    run_case(synth.SHAPES["tiny_draft"], 0, prefix, 5, seed=prefix, extra_steps=1)
+
+
+def test_llama7b_shape_two_layers():
+    # real 7B layer shape (d 4096, 32 x 128 heads, ffn 11008, vocab 32000), 2 layers,
+    # prefix 576 image rows + 64 text tokens, gamma + 1 = 5
+    mx, mean = run_case(synth.llama7b_layers(2), 576, 64, 5)
+    print("7B-shape 2-layer verify err", mx, mean)
+
+
+def test_draft_shape_sequential_steps():
+    # ~110M draft: 12 layers, d 768, 12 x 64 heads, tied embeddings; 64-token text prefix
+    spd = spd_mod()
+    shape = synth.SHAPES["draft_110m"]
+    model, wn = build_pair(shape, 3, 1, 128)
+    cfg = oracle_cfg(shape)
+    toks = synth.text_tokens(64, shape.vocab, 3)
+    cache = dec.KVCache(cfg, 128)
+    dec.forward_tokens(cfg, wn, cache, toks[:-1])
+    model.spd_prefill_tokens(0, torch.from_numpy(toks[:-1]).cuda())
+    from oracle import spec_sampling as ss
+    u = synth.uniforms((4,), 5)
+    t = int(toks[-1])
+    D = torch.empty((1, shape.vocab), dtype=torch.float32, device="cuda")
+    tok = torch.empty((1,), dtype=torch.int32, device="cuda")
+    for j in range(4):
+        ref_logits = dec.forward_tokens(cfg, wn, cache, [t])[0]
+        model.spd_draft_step(torch.tensor([[t]], dtype=torch.int32, device="cuda"), 1.0,
+                             torch.from_numpy(u[j:j + 1]).cuda(), D, tok)
+        D_gpu = D.cpu().numpy()[0]
+        D_ref = ss.softmax_probs(ref_logits, 1.0)
+        # probabilities: logits within tolerance => ratio within exp(3e-2)
+        assert abs(D_gpu.sum() - 1.0) < 1e-4
+        assert np.max(np.abs(np.log(D_gpu.astype(np.float64)) - np.log(D_ref.astype(np.float64)))) < 2 * 3e-2
+        # the token is exactly what the oracle's sampler draws from the device's own row
+        assert int(tok.item()) == ss.sample_row(D_gpu, u[j])
+        t = int(tok.item())
+    model.close()
+
+
+def test_multi_sequence_ragged_lengths_and_rollback():
+    """3 sequences with different prefix lengths verified in one call; then a
+    rollback (rejection) on each and a second call."""
+    spd = spd_mod()
+    shape = synth.SHAPES["tiny_target"]
+    lens = [9, 40, 23]
+    M = 5
+    model, wn = build_pair(shape, 7, 3, 80)
+    cfg = oracle_cfg(shape)
+    caches = []
+    for s, n in enumerate(lens):
+        x = np.concatenate([synth.image_rows(4, shape.d_model, s).astype(np.float64),
+                            dec.embed_tokens(wn, synth.text_tokens(n - 4, shape.vocab, s))])
+        c = dec.KVCache(cfg, 80)
+        dec.forward_rows(cfg, wn, c, x)
+        caches.append(c)
+        model.spd_prefill(s, torch.from_numpy(x.astype(np.float32)).cuda())
+    assert model.spd_kv_get_len(3) == lens
+    for round_ in range(2):
+        vt = np.stack([synth.text_tokens(M, shape.vocab, 50 + 10 * round_ + s) for s in range(3)])
+        out = torch.empty((3, M, shape.vocab), dtype=torch.float32, device="cuda")
+        model.spd_verify_forward(torch.from_numpy(vt).cuda(), out)
+        got = out.cpu().numpy()
+        for s in range(3):
+            ref = dec.forward_tokens(cfg, wn, caches[s], vt[s])
+            check_logits(got[s], ref, f"round {round_} seq {s}")
+        # reject: keep k + 1 of the M new positions, k differs per sequence
+        keep = [1, 3, 5]
+        new_lens = []
+        for s in range(3):
+            caches[s].truncate(caches[s].length - M + keep[s])
+            new_lens.append(caches[s].length)
+        model.spd_kv_set_len(new_lens)
+    model.close()
+
+
+def test_errors_are_reported_not_launched():
+    spd = spd_mod()
+    shape = synth.SHAPES["tiny_draft"]
+    model, _ = build_pair(shape, 1, 2, 16)
+    out = torch.empty((1, 5, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_kv_set_len([14, 0])
+    with pytest.raises(spd.SpdError) as e:
+        model.spd_verify_forward(torch.zeros((1, 5), dtype=torch.int32, device="cuda"), out)
+    assert e.value.code == spd.SPD_ERR_CAPACITY
+    assert model.spd_kv_get_len(2) == [14, 0]
+    with pytest.raises(spd.SpdError) as e:
+        model.spd_kv_set_len([17, 0])
+    assert e.value.code == spd.SPD_ERR_CAPACITY
+    out9 = torch.empty((1, 9, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_kv_set_len([0, 0])
+    with pytest.raises(spd.SpdError) as e:
+        model.spd_verify_forward(torch.zeros((1, 9), dtype=torch.int32, device="cuda"), out9)
+    assert e.value.code == spd.SPD_ERR_SHAPE
+    model.close()
+
+
+def test_verify_is_deterministic_run_to_run():
+    shape = synth.SHAPES["tiny_target"]
+    model, _ = build_pair(shape, 11, 1, 64)
+    toks = torch.from_numpy(synth.text_tokens(20, shape.vocab, 1)).cuda()
+    vt = torch.from_numpy(synth.text_tokens(5, shape.vocab, 2)).cuda()[None].contiguous()
+    outs = []
+    for _ in range(2):
+        model.spd_kv_set_len([0])
+        model.spd_prefill_tokens(0, toks)
+        out = torch.empty((1, 5, shape.vocab), dtype=torch.float32, device="cuda")
+        model.spd_verify_forward(vt, out)
+        outs.append(out.cpu())
+    assert torch.equal(outs[0], outs[1])
+    model.close()
