@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative-decoding verify step on one MI355X.
+
+A step = one pass of the hot path over one batch of synthetic input:
+spd_verify_forward (LLaMA-7B shape, gamma + 1 = 5 drafted tokens against a KV cache
+prefilled with 576 image-position embeddings + 64 text tokens, batch 1) followed by
+spd_speculative_accept on the resulting target logits and a synthetic draft's logits.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--gamma", type=int, default=4)
+    ap.add_argument("--image-rows", type=int, default=576)
+    ap.add_argument("--text-tokens", type=int, default=64)
+    ap.add_argument("--layers", type=int, default=0, help="development only: fewer layers than the 7B shape (line is marked invalid)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=4, help="layers of the oracle's verify step that are timed")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+def cpu_baseline(shape, w_host, n_prefix, M, seed):
+    """The CPU oracle's verify step, timed on a bounded sample: `cpu_layers` of the
+    layers plus the LM head, against a cache of n_prefix positions filled with
+    N(0,1) values (timing only), extrapolated to all layers."""
+    import numpy as np
+    from oracle import decoder as dec
+    from paper_2404_08856_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    w = w_host                                   # the first layers of the very weights the GPU ran
+    sub = synth.llama7b_layers(len(w["layers"]))
+    cfg = dec.DecoderConfig(sub.n_layers, sub.d_model, sub.n_heads, sub.head_dim, sub.d_ffn, sub.vocab)
+    cache = dec.KVCache(cfg, n_prefix + M)
+    rng = np.random.default_rng(seed)
+    cache.k[:, :n_prefix] = rng.standard_normal(cache.k[:, :n_prefix].shape)
+    cache.v[:, :n_prefix] = rng.standard_normal(cache.v[:, :n_prefix].shape)
+    toks = synth.text_tokens(M, sub.vocab, seed + 2)
+    times = []
+    for rep in range(3):
+        cache.length = n_prefix
+        t0 = time.perf_counter()
+        dec.forward_tokens(cfg, w, cache, toks)
+        times.append(time.perf_counter() - t0)
+    t_sub = sorted(times)[1]
+    # split the measured time into per-layer and head parts by their parameter counts
+    per_layer = 4 * sub.d_model ** 2 + 3 * sub.d_model * sub.d_ffn
+    head = sub.vocab * sub.d_model
+    t_layer = t_sub * per_layer / (sub.n_layers * per_layer + head)
+    t_head = t_sub * head / (sub.n_layers * per_layer + head)
+    t_full = t_layer * shape.n_layers + t_head
+    return {"value": M / t_full, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle verify step (float64 numpy) on {sub.n_layers} of {shape.n_layers} layers + LM head, "
+                      f"{M} rows against {n_prefix} cached positions, median of 3; extrapolated by parameter count "
+                      f"to the full model: {t_full * 1e3:.0f} ms/step"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2404_08856_amd import spd, synth
+
+    torch.cuda.set_device(0)
+    M = args.gamma + 1
+    shape = synth.SHAPES["llama7b"] if args.layers <= 0 else synth.llama7b_layers(args.layers)
+    n_prefix = args.image_rows + args.text_tokens
+    cfg = spd.make_config(shape, 1, n_prefix + M + 3)
+
+    t0 = time.time()
+    w = synth.make_weights(shape, args.seed, device="cuda")
+    model = spd.Model(cfg, w)
+    w_host = None
+    if not args.no_cpu_baseline:                 # host copy of the first layers for the oracle's timed sample
+        n_cpu = min(args.cpu_layers, shape.n_layers)
+        w_host = synth.weights_to_numpy({**{k: v for k, v in w.items() if k != "layers"}, "layers": w["layers"][:n_cpu]})
+    del w
+    torch.cuda.empty_cache()
+    print(f"[bench] model built in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+
+    # KV cache: 576 image-position embeddings ~ N(0,1), then 64 text tokens
+    img = torch.from_numpy(synth.image_rows(args.image_rows, shape.d_model, args.seed)).cuda()
+    text = torch.from_numpy(synth.text_tokens(args.text_tokens, shape.vocab, args.seed)).cuda()
+    model.spd_prefill(0, img)
+    model.spd_prefill_tokens(0, text)
+    assert model.spd_kv_get_len(1) == [n_prefix]
+
+    vt = torch.from_numpy(synth.text_tokens(M, shape.vocab, args.seed + 1)).cuda()[None].contiguous()
+    logits = torch.empty((1, M, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_verify_forward(vt, logits)
+    # synthetic draft rows: target logits + N(0, 1) noise, draft tokens drawn from them
+    g = torch.Generator(device="cuda").manual_seed(args.seed + 2)
+    draft_logits = (logits[:, :args.gamma] + torch.randn((1, args.gamma, shape.vocab), generator=g, device="cuda")).contiguous()
+    draft_tokens = torch.multinomial(torch.softmax(draft_logits[0], -1), 1, generator=g).to(torch.int32).reshape(1, args.gamma)
+    u = torch.from_numpy(synth.uniforms((1, M), args.seed + 3)).cuda()
+    k_out = torch.empty(1, dtype=torch.int32, device="cuda")
+    y_out = torch.empty(1, dtype=torch.int32, device="cuda")
+    acc_ws = torch.empty(spd.spd_accept_workspace_bytes(1, args.gamma, shape.vocab), dtype=torch.uint8, device="cuda")
+
+    def step():
+        model.spd_kv_set_len([n_prefix])            # roll the KV length back: every step verifies at the same context
+        model.spd_verify_forward(vt, logits)
+        spd.spd_speculative_accept(logits, draft_logits, draft_tokens, u, 1.0, 0, k_out, y_out, None, acc_ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+
+    # per-kernel durations (HIP events inside the library, separate pass of the same steps)
+    model.spd_trace_enable(True)
+    trace_steps = min(args.steps, 20)
+    for _ in range(trace_steps):
+        step()
+    trace = model.spd_trace_read()
+    model.spd_trace_enable(False)
+    kinds = {k: {"ms_per_launch": (ms / n if n else None), "launches_per_step": n / trace_steps, "ms_per_step": ms / trace_steps}
+             for k, (ms, n) in trace.items()}
+
+    HD = shape.n_heads * shape.head_dim
+    weight_bytes = shape.streamed_weight_bytes()
+    kv_bytes = shape.n_layers * 2 * (n_prefix + M) * HD * 2
+    accept_bytes = (2 * args.gamma + 1) * shape.vocab * 4
+    step_bytes = weight_bytes + kv_bytes + accept_bytes
+    gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel: the gate|up projection instance of the skinny GEMM (42.6% of the bytes)
+    gu_bytes = 2 * shape.d_ffn * shape.d_model * 2
+    gu_ms = kinds["gate_up"]["ms_per_launch"]
+    gu_gbps = gu_bytes / (gu_ms * 1e-3) / 1e9
+    per_kind_bytes = {"qkv": 3 * HD * shape.d_model * 2, "o": shape.d_model * HD * 2, "gate_up": gu_bytes,
+                      "down": shape.d_model * shape.d_ffn * 2, "lm_head": shape.vocab * shape.d_model * 2,
+                      "attention": 2 * (n_prefix + M) * HD * 2}
+    for k, b in per_kind_bytes.items():
+        if kinds[k]["ms_per_launch"]:
+            kinds[k]["GBps"] = b / (kinds[k]["ms_per_launch"] * 1e-3) / 1e9
+
+    out = {
+        "metric": "7B verify-step verified tokens/sec (gamma=4), with achieved HBM GB/s",
+        "value": M / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama7b_verify_step: 32 layers d=4096 32x128 heads ffn 11008 vocab 32000, bf16 N(0,0.02) weights, "
+                               f"KV prefix {args.image_rows} image rows + {args.text_tokens} text tokens, gamma+1={M} tokens, batch 1, "
+                               "then speculative accept (logit inputs, temperature 1)",
+                   "n_layers": shape.n_layers, "gamma": args.gamma, "prefix_positions": n_prefix, "batch": 1},
+        "hbm_GBps": gbps, "hbm_frac_of_peak": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_step": step_bytes,
+        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel (gate|up projection + SwiGLU instance)",
+                     "achieved": gu_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gu_gbps / HBM_PEAK_GBPS,
+                     "traffic": None, "bytes_per_launch": gu_bytes, "ms_per_launch": gu_ms},
+        "kernels": kinds,
+    }
+    if args.layers > 0:
+        out["invalid"] = "development run with fewer layers than the 7B shape"
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, w_host, n_prefix, M, args.seed)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -29,8 +29,8 @@
  *     workspace live in caller-owned buffers whose sizes spd_model_bytes()
  *     reports.  The model borrows them until spd_model_destroy().
  *   - Shapes: d_model % 32 == 0, head_dim in {64, 128}, (n_heads*head_dim) % 16
- *     == 0, d_ffn % 8 == 0, vocab % 16 == 0, rows per call (n_seqs * M) <= 64,
- *     M <= 8.  Violations return SPD_ERR_SHAPE before anything is launched.
+ *     == 0, d_ffn % 8 == 0, vocab % 16 == 0, max_positions <= 8192, rows per call
+ *     (n_seqs * M) <= 64, M <= 8.  Violations return SPD_ERR_SHAPE before anything is launched.
  */
 #ifndef SPD_H
 #define SPD_H
@@ -181,6 +181,19 @@ int32_t spd_speculative_accept(const float *target, const float *draft, const in
                                float temperature, uint32_t flags, int32_t *n_accepted_out,
                                int32_t *next_token_out, float *accept_prob_out,
                                void *workspace, size_t workspace_bytes, void *stream);
+
+/* Tracing aid (not part of the method).  While enabled, every kernel launch group of
+ * this model's forward passes is bracketed by a pair of HIP events on the caller's
+ * stream (host-side event objects only: no device memory).  spd_trace_read WAITS for
+ * the recorded events (the one call here that blocks the host), adds the elapsed
+ * milliseconds and launch counts per kind into h_ms_sum[n_kinds] / h_count[n_kinds] and
+ * forgets them.  Kinds: 0 QKV projection, 1 O projection, 2 gate|up projection + SwiGLU,
+ * 3 down projection, 4 LM head, 5 RoPE + KV append + attention, 6 unused (RMSNorm is
+ * folded into the projections), 7 input rows (embedding gather).  The events perturb the stream slightly: time whole
+ * steps with tracing off. */
+#define SPD_TRACE_KINDS 8
+int32_t spd_trace_enable(spd_model *model, int32_t enable);
+int32_t spd_trace_read(spd_model *model, int32_t n_kinds, double *h_ms_sum, int32_t *h_count);
 
 #ifdef __cplusplus
 }

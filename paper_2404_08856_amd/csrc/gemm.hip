@@ -74,7 +74,7 @@ __device__ __forceinline__ f32x4_t mfma_bf16(const uint4 &a, const uint4 &b, f32
 }
 
 __device__ __forceinline__ uint4 load_stream(const uint4 *p) {
-    // weights are read exactly once per step: mark the load non-temporal
+    // weights are read exactly once per step: non-temporal loads (measured: +15% on a pure read stream)
     typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
     u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
     return uint4{v.x, v.y, v.z, v.w};
@@ -86,122 +86,299 @@ struct GemmKernelArgs {
     int KS, n_tiles, rows;
     float *Y;
     int ldy;
-    uint16_t *Xout;
+    const float *ssq_in;      // [ssq_in_parts][64] partial sums of squares of the input rows, or NULL
+    int ssq_in_parts;
+    float inv_d, eps;         // RMSNorm: 1 / sqrt(sum * inv_d + eps)
+    const float *gain_next;   // RESIDUAL: gain of the norm that follows, or NULL
+    uint16_t *Xnext;          // RESIDUAL: packed (h * gain_next), K = N
+    float *ssq_out;           // RESIDUAL: [n_tiles][64] partial sums of squares of the new h
+    uint16_t *Xout;           // SWIGLU: packed activations, K = N / 2
     int KS_out;
 };
 
-// One workgroup = R consecutive 16-row tiles of W; its WAVES waves split the K range.
-template <int NG, int R, int WAVES, int EPI>
-__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(GemmKernelArgs a) {
-    constexpr int U = (R * NG >= 4) ? 4 : 8;          // 1 KiB weight blocks in flight per tile
+// Persistent workgroups: workgroup b owns tiles b, b + gridDim.x, ...; its WAVES waves split
+// the K range of every tile.  Each wave keeps a ring of U weight blocks (and the matching
+// activation blocks) in flight: right after a block has been consumed by the matrix core its
+// register slot is refilled with the block U steps ahead -- of the same tile or of the
+// workgroup's next tile -- so the HBM stream never drains at a tile boundary, during the
+// cross-wave reduction or during the epilogue.
+template <int NG, int WAVES, int EPI, int U>
+__global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs a) {
     const int lane = threadIdx.x & 63;
-    const int w = threadIdx.x >> 6;
-    const int tile0 = blockIdx.x * R;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known uniform
     const int KS = a.KS;
     const int s0 = (int)(((long)KS * w) / WAVES);
     const int s1 = (int)(((long)KS * (w + 1)) / WAVES);
+    const int ns = s1 - s0;
+    const int nfull = ns / U, rem = ns - nfull * U;
+    const int G = gridDim.x;
 
-    f32x4_t acc[R][NG];
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int g = 0; g < NG; ++g) acc[r][g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    __shared__ float red[2][WAVES][NG][16][8];
+    __shared__ float inv_s[kMaxRows];
 
-    const uint4 *wp[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) wp[r] = a.W + (size_t)(tile0 + r) * KS * 64 + lane;
-    const uint4 *xp = a.X + lane;
-
-    int s = s0;
-    for (; s + U <= s1; s += U) {
-        uint4 av[R][U], bv[NG][U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-#pragma unroll
-            for (int r = 0; r < R; ++r) av[r][u] = load_stream(wp[r] + (size_t)(s + u) * 64);
-#pragma unroll
-            for (int g = 0; g < NG; ++g) bv[g][u] = xp[((size_t)g * KS + s + u) * 64];
-        }
+    uint4 av[U], bv[NG][U];
+    int t = blockIdx.x;
+    if (t < a.n_tiles) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
+            if (u < ns) {
+                av[u] = load_stream(a.W + ((size_t)t * KS + s0 + u) * 64 + lane);
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int g = 0; g < NG; ++g) acc[r][g] = mfma_bf16(av[r][u], bv[g][u], acc[r][g]);
+                for (int g = 0; g < NG; ++g) bv[g][u] = a.X[((size_t)g * KS + s0 + u) * 64 + lane];
+            }
     }
-    for (; s < s1; ++s) {
-        uint4 av[R], bv[NG];
+    // 1 / rms of every input row from the producer's per-tile partial sums (fixed order)
+    if (a.ssq_in) {
+        for (int r = w; r < a.rows; r += WAVES) {
+            float sum = 0.f;
+            for (int p = lane; p < a.ssq_in_parts; p += 64) sum += a.ssq_in[(size_t)p * kMaxRows + r];
 #pragma unroll
-        for (int r = 0; r < R; ++r) av[r] = load_stream(wp[r] + (size_t)s * 64);
-#pragma unroll
-        for (int g = 0; g < NG; ++g) bv[g] = xp[((size_t)g * KS + s) * 64];
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int g = 0; g < NG; ++g) acc[r][g] = mfma_bf16(av[r], bv[g], acc[r][g]);
+            for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+            if (lane == 0) inv_s[r] = 1.0f / sqrtf(sum * a.inv_d + a.eps);
+        }
+    } else {
+        if (threadIdx.x < kMaxRows) inv_s[threadIdx.x] = 1.0f;
     }
+    __syncthreads();
 
-    // D[n = 4 (lane / 16) + v][c = lane % 16]; columns c and c + 8 are head and tail of row c.
-    __shared__ float red[WAVES][R][NG][16][8];
+    int parity = 0;
+    for (; t < a.n_tiles; t += G, parity ^= 1) {
+        const int tn = t + G;
+        // epilogue element of this thread (threads < NG * 128): fetch the old residual early
+        const int e = threadIdx.x;
+        const int en = e & 15, em = (e >> 4) & 7, eg = e >> 7;
+        const int erow = eg * 8 + em;
+        const bool e_active = (EPI != EPI_SWIGLU) ? (e < NG * 128 && erow < a.rows)
+                                                  : (e < NG * 128 && erow < a.rows && en < 8);
+        float hold = 0.f;
+        if (EPI == EPI_RESIDUAL && e_active) hold = a.Y[(size_t)erow * a.ldy + (size_t)t * 16 + en];
+
+        f32x4_t acc[NG];
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+        for (int g = 0; g < NG; ++g) acc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        // Steady state: straight-line code, no branch between a matrix-core step and the
+        // refill of its slot, so that the compiler can wait for exactly the oldest block.
+        // A slot whose next block lies beyond the workgroup's last tile re-reads an
+        // activation block (cache hit, result unused) instead of branching.
+        const bool has_next = tn < a.n_tiles;
+        for (int c = 0; c < nfull; ++c) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int g = 0; g < NG; ++g) acc[g] = mfma_bf16(av[u], bv[g][u], acc[g]);
+                const int i2 = c * U + u + U;
+                const bool same = i2 < ns;
+                const uint4 *wsrc = (same || has_next) ? a.W : a.X;
+                const size_t woff = same ? ((size_t)t * KS + s0 + i2) : (has_next ? ((size_t)tn * KS + s0 + u) : (size_t)0);
+                av[u] = load_stream(wsrc + woff * 64 + lane);
+                const int xs = same ? s0 + i2 : s0 + u;
+#pragma unroll
+                for (int g = 0; g < NG; ++g) bv[g][u] = a.X[((size_t)g * KS + xs) * 64 + lane];
+                __builtin_amdgcn_sched_barrier(0);        // keep "consume slot, refill slot" in program order
+            }
+        }
+        if (rem) {                                        // ragged tail of this wave's K range
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (u < rem) {
+#pragma unroll
+                    for (int g = 0; g < NG; ++g) acc[g] = mfma_bf16(av[u], bv[g][u], acc[g]);
+                    if (has_next) {
+                        av[u] = load_stream(a.W + ((size_t)tn * KS + s0 + u) * 64 + lane);
+#pragma unroll
+                        for (int g = 0; g < NG; ++g) bv[g][u] = a.X[((size_t)g * KS + s0 + u) * 64 + lane];
+                    }
+                }
+            }
+        }
+        // D[n = 4 (lane / 16) + v][c = lane % 16]; columns c and c + 8 are head and tail of row c
 #pragma unroll
         for (int g = 0; g < NG; ++g)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                float x = acc[r][g][v];
+                float x = acc[g][v];
                 float y = __shfl_xor(x, 8);
-                if ((lane & 15) < 8) red[w][r][g][4 * (lane >> 4) + v][lane & 7] = x + y;
+                if ((lane & 15) < 8) red[parity][w][g][4 * (lane >> 4) + v][lane & 7] = x + y;
             }
-    __syncthreads();
+        __syncthreads();
 
-    if (EPI == EPI_SWIGLU) {
-        // rows 0..7 of a tile are gate features f0..f0+7, rows 8..15 the matching up features
-        for (int e = threadIdx.x; e < R * NG * 64; e += WAVES * 64) {
-            int n = e & 7, m = (e >> 3) & 7, g = (e >> 6) % NG, r = e / (64 * NG);
-            float gate = 0.f, up = 0.f;
+        if (EPI == EPI_SWIGLU) {
+            // rows 0..7 of a tile are gate features f0..f0+7, rows 8..15 the matching up features
+            if (e_active) {
+                float gate = 0.f, up = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < WAVES; ++ww) {      // fixed order: deterministic
-                gate += red[ww][r][g][n][m];
-                up += red[ww][r][g][n + 8][m];
-            }
-            int row = g * 8 + m;
-            if (row < a.rows) {
+                for (int ww = 0; ww < WAVES; ++ww) {            // fixed order: deterministic
+                    gate += red[parity][ww][eg][en][em];
+                    up += red[parity][ww][eg][en + 8][em];
+                }
+                gate *= inv_s[erow];
+                up *= inv_s[erow];
                 float val = gate / (1.0f + expf(-gate)) * up;
-                int f = (tile0 + r) * 8 + n;
+                int f = t * 8 + en;
                 uint16_t hi, lo;
                 split_hi_lo(val, hi, lo);
-                a.Xout[xpack_index(row, f, a.KS_out, 0)] = hi;
-                a.Xout[xpack_index(row, f, a.KS_out, 1)] = lo;
+                a.Xout[xpack_index(erow, f, a.KS_out, 0)] = hi;
+                a.Xout[xpack_index(erow, f, a.KS_out, 1)] = lo;
             }
-        }
-    } else {
-        for (int e = threadIdx.x; e < R * NG * 128; e += WAVES * 64) {
-            int n = e & 15, m = (e >> 4) & 7, g = (e >> 7) % NG, r = e / (128 * NG);
+        } else if (e < NG * 128) {
             float sum = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < WAVES; ++ww) sum += red[ww][r][g][n][m];
-            int row = g * 8 + m;
-            if (row < a.rows) {
-                float *y = a.Y + (size_t)row * a.ldy + (size_t)(tile0 + r) * 16 + n;
-                if (EPI == EPI_RESIDUAL) *y += sum; else *y = sum;
+            for (int ww = 0; ww < WAVES; ++ww) sum += red[parity][ww][eg][en][em];
+            sum *= inv_s[erow < kMaxRows ? erow : 0];
+            if (EPI == EPI_STORE) {
+                if (e_active) a.Y[(size_t)erow * a.ldy + (size_t)t * 16 + en] = sum;
+            } else {
+                float hnew = e_active ? hold + sum : 0.f;
+                const int col = t * 16 + en;
+                if (e_active) {
+                    a.Y[(size_t)erow * a.ldy + col] = hnew;
+                    if (a.gain_next) {
+                        uint16_t hi, lo;
+                        split_hi_lo(hnew * a.gain_next[col], hi, lo);
+                        const int KSn = a.n_tiles / 2;               // N / 32
+                        a.Xnext[xpack_index(erow, col, KSn, 0)] = hi;
+                        a.Xnext[xpack_index(erow, col, KSn, 1)] = lo;
+                    }
+                }
+                // sum of squares of the 16 new values of this row in this tile (lanes en = 0..15)
+                float sq = hnew * hnew;
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
+                if (a.ssq_out && en == 0 && e_active) a.ssq_out[(size_t)t * kMaxRows + erow] = sq;
+            }
+        }
+        // no second barrier: the next tile writes the other half of `red`
+    }
+}
+
+// Fast path for up to 8 rows (one row group) when every wave owns exactly NB K-steps of a
+// tile (KS == WAVES * NB): the wave's slice of the activation operand stays in registers
+// for the whole kernel -- it is the same for every tile -- so the only loads in the loop are
+// the weight blocks.  (Measured on a read probe of the same shape: re-reading the
+// activation blocks per tile from L2 costs 15-20% of the achieved HBM bandwidth.)
+// The tile body is straight-line code: NB matrix-core steps, each followed by the refill
+// of its register slot with the block U steps ahead (same tile, or the workgroup's next
+// tile), so all of a wave's loads for the next tile are in flight while the tile is
+// reduced across waves and written out.
+template <int WAVES, int EPI, int NB, int U>
+__global__ __launch_bounds__(WAVES * 64, (NB <= 8 ? 4 : 2)) void gemm_regb_kernel(GemmKernelArgs a) {
+    static_assert(NB % U == 0, "ring must divide the per-wave K range");
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int KS = a.KS;                                  // == WAVES * NB
+    const int s0 = w * NB;
+    const int G = gridDim.x;
+
+    __shared__ float red[2][WAVES][16][8];
+
+    int t = blockIdx.x;
+    if (t >= a.n_tiles) return;
+
+    uint4 av[U], bv[NB];
+#pragma unroll
+    for (int u = 0; u < U; ++u) av[u] = load_stream(a.W + ((size_t)t * KS + s0 + u) * 64 + lane);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) bv[i] = a.X[(size_t)(s0 + i) * 64 + lane];
+
+    // Epilogue role of this thread: pairs of waves take turns (tile k is finished by waves
+    // 2 (k mod WAVES/2) and +1); a thread always handles output row em and column en.
+    const int en = lane & 15, em = (w & 1) * 4 + (lane >> 4);
+    const bool row_ok = em < a.rows;
+    float inv_row = 1.0f;
+    if (a.ssq_in) {                                       // 1 / rms of row em from the per-tile partial sums
+        float sum = 0.f;
+        if (row_ok)
+            for (int p = en; p < a.ssq_in_parts; p += 16) sum += a.ssq_in[(size_t)p * kMaxRows + em];
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        inv_row = 1.0f / sqrtf(sum * a.inv_d + a.eps);
+    }
+
+    int parity = 0, turn = 0;
+    for (; t < a.n_tiles; t += G, parity ^= 1, turn = (turn + 2) % WAVES) {
+        const int tn = t + G;
+        const bool has_next = tn < a.n_tiles;
+        const bool my_turn = (w == turn) || (w == turn + 1);
+        const bool e_active = my_turn && row_ok && (EPI != EPI_SWIGLU || en < 8);
+        float hold = 0.f;
+        if (EPI == EPI_RESIDUAL && e_active) hold = a.Y[(size_t)em * a.ldy + (size_t)t * 16 + en];
+
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        const uint4 *wnext = has_next ? a.W + ((size_t)tn * KS + s0) * 64 : a.X;   // past the end: harmless re-read
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            acc = mfma_bf16(av[i % U], bv[i], acc);
+            if (i + U < NB) av[i % U] = load_stream(a.W + ((size_t)t * KS + s0 + i + U) * 64 + lane);
+            else av[i % U] = load_stream(wnext + (size_t)(has_next ? (i + U - NB) : 0) * 64 + lane);
+            __builtin_amdgcn_sched_barrier(0);            // keep "consume slot, refill slot" in program order
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float x = acc[v];
+            float y = __shfl_xor(x, 8);
+            if ((lane & 15) < 8) red[parity][w][4 * (lane >> 4) + v][lane & 7] = x + y;
+        }
+        __syncthreads();
+        if (!my_turn) continue;
+
+        if (EPI == EPI_SWIGLU) {
+            if (e_active) {
+                float gate = 0.f, up = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ++ww) {
+                    gate += red[parity][ww][en][em];
+                    up += red[parity][ww][en + 8][em];
+                }
+                gate *= inv_row;
+                up *= inv_row;
+                float val = gate / (1.0f + expf(-gate)) * up;
+                int f = t * 8 + en;
+                uint16_t hi, lo;
+                split_hi_lo(val, hi, lo);
+                a.Xout[xpack_index(em, f, a.KS_out, 0)] = hi;
+                a.Xout[xpack_index(em, f, a.KS_out, 1)] = lo;
+            }
+        } else {
+            float sum = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < WAVES; ++ww) sum += red[parity][ww][en][em];
+            sum *= inv_row;
+            const int col = t * 16 + en;
+            if (EPI == EPI_STORE) {
+                if (e_active) a.Y[(size_t)em * a.ldy + col] = sum;
+            } else {
+                float hnew = e_active ? hold + sum : 0.f;
+                if (e_active) {
+                    a.Y[(size_t)em * a.ldy + col] = hnew;
+                    if (a.gain_next) {
+                        uint16_t hi, lo;
+                        split_hi_lo(hnew * a.gain_next[col], hi, lo);
+                        const int KSn = a.n_tiles / 2;
+                        a.Xnext[xpack_index(em, col, KSn, 0)] = hi;
+                        a.Xnext[xpack_index(em, col, KSn, 1)] = lo;
+                    }
+                }
+                float sq = hnew * hnew;
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
+                if (a.ssq_out && en == 0 && e_active) a.ssq_out[(size_t)t * kMaxRows + em] = sq;
             }
         }
     }
 }
 
-template <int NG, int R, int WAVES>
-static hipError_t launch_epi(const GemmKernelArgs &k, int epilogue, hipStream_t stream) {
-    dim3 grid(k.n_tiles / R), block(WAVES * 64);
+template <int WAVES, int NB, int U>
+static hipError_t launch_regb(const GemmKernelArgs &k, int epilogue, int grid, hipStream_t stream) {
+    dim3 g(grid), block(WAVES * 64);
     switch (epilogue) {
         case EPI_STORE:
-            hipLaunchKernelGGL((gemm_skinny_kernel<NG, R, WAVES, EPI_STORE>), grid, block, 0, stream, k);
+            hipLaunchKernelGGL((gemm_regb_kernel<WAVES, EPI_STORE, NB, U>), g, block, 0, stream, k);
             break;
         case EPI_RESIDUAL:
-            hipLaunchKernelGGL((gemm_skinny_kernel<NG, R, WAVES, EPI_RESIDUAL>), grid, block, 0, stream, k);
+            hipLaunchKernelGGL((gemm_regb_kernel<WAVES, EPI_RESIDUAL, NB, U>), g, block, 0, stream, k);
             break;
         case EPI_SWIGLU:
-            hipLaunchKernelGGL((gemm_skinny_kernel<NG, R, WAVES, EPI_SWIGLU>), grid, block, 0, stream, k);
+            hipLaunchKernelGGL((gemm_regb_kernel<WAVES, EPI_SWIGLU, NB, U>), g, block, 0, stream, k);
             break;
         default:
             return hipErrorInvalidValue;
@@ -209,24 +386,37 @@ static hipError_t launch_epi(const GemmKernelArgs &k, int epilogue, hipStream_t 
     return hipGetLastError();
 }
 
-template <int NG>
-static hipError_t launch_ng(const GemmKernelArgs &k, int epilogue, GemmTuning t, hipStream_t stream) {
-    if (NG == 1) {
-        if (t.tiles_per_wg == 2) {
-            if (t.waves == 4) return launch_epi<NG, 2, 4>(k, epilogue, stream);
-            if (t.waves == 8) return launch_epi<NG, 2, 8>(k, epilogue, stream);
-            return launch_epi<NG, 2, 16>(k, epilogue, stream);
-        }
-        if (t.waves == 4) return launch_epi<NG, 1, 4>(k, epilogue, stream);
-        if (t.waves == 8) return launch_epi<NG, 1, 8>(k, epilogue, stream);
-        return launch_epi<NG, 1, 16>(k, epilogue, stream);
+template <int NG, int WAVES, int U>
+static hipError_t launch_epi(const GemmKernelArgs &k, int epilogue, int grid, hipStream_t stream) {
+    dim3 g(grid), block(WAVES * 64);
+    switch (epilogue) {
+        case EPI_STORE:
+            hipLaunchKernelGGL((gemm_stream_kernel<NG, WAVES, EPI_STORE, U>), g, block, 0, stream, k);
+            break;
+        case EPI_RESIDUAL:
+            hipLaunchKernelGGL((gemm_stream_kernel<NG, WAVES, EPI_RESIDUAL, U>), g, block, 0, stream, k);
+            break;
+        case EPI_SWIGLU:
+            hipLaunchKernelGGL((gemm_stream_kernel<NG, WAVES, EPI_SWIGLU, U>), g, block, 0, stream, k);
+            break;
+        default:
+            return hipErrorInvalidValue;
     }
-    if (t.waves == 4) return launch_epi<NG, 1, 4>(k, epilogue, stream);
-    return launch_epi<NG, 1, 8>(k, epilogue, stream);
+    return hipGetLastError();
+}
+
+// Largest divisor of n_tiles that is <= cap (equal work per workgroup), at least cap / 2
+// if one exists; otherwise cap itself (some workgroups then own one tile more).
+static int pick_grid(int n_tiles, int cap) {
+    if (n_tiles <= cap) return n_tiles;
+    for (int g = cap; g >= cap / 2; --g)
+        if (n_tiles % g == 0) return g;
+    return cap;
 }
 
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStream_t stream) {
     if (a.N % 16 != 0 || a.rows < 1 || a.rows > kMaxRows) return hipErrorInvalidValue;
+    if (epilogue == EPI_RESIDUAL && a.gain_next && (a.N % 32 != 0)) return hipErrorInvalidValue;
     GemmKernelArgs k;
     k.W = (const uint4 *)a.W;
     k.X = (const uint4 *)a.X;
@@ -235,20 +425,52 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStre
     k.rows = a.rows;
     k.Y = a.Y;
     k.ldy = a.ldy;
+    k.ssq_in = a.ssq_in;
+    k.ssq_in_parts = a.ssq_in_parts;
+    k.inv_d = a.K > 0 ? 1.0f / (float)a.K : 0.f;
+    k.eps = a.eps;
+    k.gain_next = a.gain_next;
+    k.Xnext = (uint16_t *)a.Xnext;
+    k.ssq_out = a.ssq_out;
     k.Xout = (uint16_t *)a.Xout;
     k.KS_out = (a.K_out + 31) / 32;
-    int groups = (a.rows + 7) / 8;
-    // normalise the tuning to an instantiated variant
-    if (tune.waves != 4 && tune.waves != 8 && tune.waves != 16) tune.waves = 8;
-    if (groups > 1) {
-        tune.tiles_per_wg = 1;
-        if (tune.waves == 16) tune.waves = 8;
+    const int groups = (a.rows + 7) / 8;
+    int waves = tune.waves;
+    if (waves != 4 && waves != 8 && waves != 16) waves = 8;
+    if (groups > 1 && waves == 16) waves = 8;            // 16 waves need <= 128 VGPRs: only the 1-group ring fits
+    if (groups > 4) waves = 4;
+    int cap = tune.grid_cap > 0 ? tune.grid_cap : (waves == 4 ? 1024 : (waves == 8 ? 512 : 256));
+    const int grid = pick_grid(k.n_tiles, cap);
+    if (groups == 1 && !tune.no_regb) {
+        // register-resident activation slice: every wave owns exactly 8 or 16 K-steps.
+        // Resident workgroups per CU follow from the register budget of each variant.
+        auto grid_for = [&](int per_cu) { return pick_grid(k.n_tiles, tune.grid_cap > 0 ? tune.grid_cap : 256 * per_cu); };
+        if (waves == 16 && k.KS == 16 * 8) return launch_regb<16, 8, 8>(k, epilogue, grid_for(1), stream);
+        if (waves == 8 && k.KS == 8 * 16) return launch_regb<8, 16, 8>(k, epilogue, grid_for(1), stream);
+        if (waves == 8 && k.KS == 8 * 8) return launch_regb<8, 8, 8>(k, epilogue, grid_for(2), stream);
+        if (waves == 4 && k.KS == 4 * 8) return launch_regb<4, 8, 8>(k, epilogue, grid_for(4), stream);
+        if (waves == 4 && k.KS == 4 * 16) return launch_regb<4, 16, 8>(k, epilogue, grid_for(2), stream);
     }
-    if (tune.tiles_per_wg != 2 || (k.n_tiles % 2) != 0) tune.tiles_per_wg = 1;
-    if (groups == 1) return launch_ng<1>(k, epilogue, tune, stream);
-    if (groups == 2) return launch_ng<2>(k, epilogue, tune, stream);
-    if (groups <= 4) return launch_ng<4>(k, epilogue, tune, stream);
-    return launch_ng<8>(k, epilogue, tune, stream);
+#define SPD_GEMM_CASE(NG_, W_, U_) return launch_epi<NG_, W_, U_>(k, epilogue, grid, stream)
+    if (groups == 1) {
+        if (tune.ring == 16 && waves != 16) {
+            if (waves == 4) SPD_GEMM_CASE(1, 4, 16);
+            SPD_GEMM_CASE(1, 8, 16);
+        }
+        if (waves == 4) SPD_GEMM_CASE(1, 4, 8);
+        if (waves == 8) SPD_GEMM_CASE(1, 8, 8);
+        SPD_GEMM_CASE(1, 16, 8);
+    }
+    if (groups == 2) {
+        if (waves == 4) SPD_GEMM_CASE(2, 4, 8);
+        SPD_GEMM_CASE(2, 8, 8);
+    }
+    if (groups <= 4) {
+        if (waves == 4) SPD_GEMM_CASE(4, 4, 4);
+        SPD_GEMM_CASE(4, 8, 4);
+    }
+    SPD_GEMM_CASE(8, 4, 4);
+#undef SPD_GEMM_CASE
 }
 
 }  // namespace spd

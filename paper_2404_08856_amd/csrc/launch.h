@@ -20,26 +20,36 @@ size_t packed_matrix_bytes(int N, int K);
 
 // ---- skinny weight-streaming GEMM -------------------------------------------------
 enum Epilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
-struct GemmTuning { int waves; int tiles_per_wg; };
+struct GemmTuning { int waves; int grid_cap; int ring; int no_regb; };   // 0 = default for grid_cap / ring
 struct GemmArgs {
     const void *W;        // packed weights [N, K]
     const void *X;        // packed activations (B operand blocks), K columns
     int N, K;             // logical sizes (N % 16 == 0)
     int rows;             // valid activation rows (<= 64)
-    float *Y;             // STORE: Y[row, n] = acc ; RESIDUAL: Y[row, n] += acc   (ld = ldy)
+    float *Y;             // STORE: Y[row, n] = s * acc ; RESIDUAL: Y[row, n] += acc   (ld = ldy)
     int ldy;
+    // RMSNorm folded into the GEMM: X holds (h * gain) un-normalised; the row scale
+    // s = 1 / sqrt(sum_sq / K + eps) is applied to the accumulator.  ssq_in[parts][64] holds
+    // partial sums of squares per row (NULL: s = 1).
+    const float *ssq_in;
+    int ssq_in_parts;
+    float eps;
+    // RESIDUAL only: also emit what the next norm + GEMM needs from the new h (N % 32 == 0):
+    const float *gain_next;   // gain of the following RMSNorm, or NULL
+    void *Xnext;              // packed (h_new * gain_next), K = N
+    float *ssq_out;           // [N / 16][64] per-tile sums of squares of h_new
     void *Xout;           // SWIGLU: packed activations with K_out = N / 2 columns
     int K_out;
 };
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStream_t stream);
 
 // ---- row-wise kernels -------------------------------------------------------------
-// h[row, :] = float(E[tokens[row], :]); token ids are clamped into [0, vocab)
-hipError_t launch_embed_gather(const void *embed_bf16, const int32_t *tokens, int rows, int d, int vocab,
-                               float *h, hipStream_t stream);
-// xpack <- head/tail split of RMSNorm(h[row, :]) * gain, rows <= 64, d % 32 == 0
-hipError_t launch_rmsnorm_pack(const float *h, const float *gain, int rows, int d, float eps,
-                               void *xpack, hipStream_t stream);
+// Input rows of a forward: h[row, :] = float(E[tokens[row], :]) (token ids clamped into
+// [0, vocab)) or h[row, :] = embeds[row, :]; also writes the packed (h * gain) operand of
+// the first QKV projection and the sum of squares of every row (ssq[row], one part).
+hipError_t launch_input_rows(const void *embed_bf16, const int32_t *tokens, const float *embeds, int rows,
+                             int d, int vocab, const float *gain, float *h, void *xpack, float *ssq,
+                             hipStream_t stream);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t stream);
 
 // ---- attention ----------------------------------------------------------------------
@@ -50,6 +60,7 @@ struct AttnArgs {
     float *part_o;           // [n_seqs, H, n_split, 8, dh]
     float *part_ml;          // [n_seqs, H, n_split, 8, 2]  (max, sum)
     void *xout;              // packed activations, K = H * dh (attention output)
+    int32_t *counters;       // [n_seqs * H] zero between launches (last-arriving slice merges)
     int n_seqs, M, H, dh, max_positions, n_split, split_len;
     SeqLens lens;            // KV length of every sequence before this call
 };

@@ -40,6 +40,7 @@ int32_t fail(int32_t code, const char *fmt, ...) {
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 constexpr int kMinSplit = 32;      // smallest key-slice length the attention launch uses
+constexpr int kMaxSplit = 128;     // largest; with at most 64 slices this bounds max_positions at 8192
 
 struct Layout {                    // byte offsets inside the three buffers
     // packed
@@ -49,7 +50,7 @@ struct Layout {                    // byte offsets inside the three buffers
     // kv
     size_t kv_layer_stride, kv_half, kv_total;
     // workspace
-    size_t h, qkv, xn, xo, xf, part_o, part_ml, rope, logits, ws_total;
+    size_t h, qkv, xn, xo, xf, part_o, part_ml, rope, logits, ssq_a, ssq_b, counters, ws_total;
     int n_split_max;
 };
 
@@ -65,6 +66,7 @@ int32_t check_shape(const spd_model_config &c) {
     if (c.d_ffn % 8) return fail(SPD_ERR_SHAPE, "d_ffn %d must be a multiple of 8", c.d_ffn);
     if (c.vocab % 16) return fail(SPD_ERR_SHAPE, "vocab %d must be a multiple of 16", c.vocab);
     if (c.max_seqs > SPD_MAX_ROWS) return fail(SPD_ERR_SHAPE, "max_seqs %d exceeds %d", c.max_seqs, SPD_MAX_ROWS);
+    if (c.max_positions > 64 * kMaxSplit) return fail(SPD_ERR_SHAPE, "max_positions %d exceeds %d", c.max_positions, 64 * kMaxSplit);
     if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return fail(SPD_ERR_SHAPE, "bad rms_eps / rope_theta");
     return SPD_OK;
 }
@@ -102,23 +104,30 @@ void make_layout(const spd_model_config &c, Layout &L) {
     L.part_ml = take((size_t)c.max_seqs * c.n_heads * L.n_split_max * 8 * 2 * 4);
     L.rope = take((size_t)c.max_positions * (c.head_dim / 2) * 2 * 4);
     L.logits = take((size_t)kMaxRows * V * 4);
+    L.ssq_a = take((size_t)(d / 16) * kMaxRows * 4);
+    L.ssq_b = take((size_t)(d / 16) * kMaxRows * 4);
+    L.counters = take((size_t)c.max_seqs * c.n_heads * 4);
     L.ws_total = off;
 }
 
 GemmTuning default_tuning(int N, int K) {
-    // Enough workgroups to cover 256 CUs a few times over, and K long enough per wave to
-    // keep several 1 KiB loads in flight: fewer tiles -> more waves splitting K.
-    int tiles = N / 16;
+    // Measured on MI355X at 5 rows: for K = 4096 (128 K-steps) 8 waves x 16 steps with the
+    // activation slice held in registers and one persistent workgroup per CU is fastest;
+    // otherwise fewer tiles -> more waves splitting K.
+    int tiles = N / 16, KS = (K + 31) / 32;
     GemmTuning t;
-    t.tiles_per_wg = 1;
-    if (tiles >= 1024) t.waves = 4;
+    t.grid_cap = 0;
+    t.ring = 8;
+    t.no_regb = 0;
+    if (KS == 128 || KS == 64) t.waves = 8;
+    else if (KS == 32) t.waves = 4;
+    else if (tiles >= 1024) t.waves = 4;
     else if (tiles >= 512) t.waves = 8;
     else t.waves = 16;
-    (void)K;
     return t;
 }
 
-// SPD_TUNE="qkv:8:1,o:16:1,gu:4:2,down:16:1,lm:8:1"  (waves:tiles_per_wg), for sweeps
+// SPD_TUNE="qkv:8:512:8,o:16:256:8,gu:4:1024:8,down:16:0:8,lm:8:0:16"  (waves:grid_cap:ring), for sweeps
 void env_tuning(const char *name, GemmTuning &t) {
     const char *env = getenv("SPD_TUNE");
     if (!env) return;
@@ -129,8 +138,10 @@ void env_tuning(const char *name, GemmTuning &t) {
         if (q == std::string::npos) q = s.size();
         std::string item = s.substr(p, q - p);
         if (item.compare(0, key.size(), key) == 0) {
-            int w = 0, r = 0;
-            if (sscanf(item.c_str() + key.size(), "%d:%d", &w, &r) == 2) { t.waves = w; t.tiles_per_wg = r; }
+            int w = 0, cap = 0, ring = 8, noregb = 0;
+            if (sscanf(item.c_str() + key.size(), "%d:%d:%d:%d", &w, &cap, &ring, &noregb) >= 1) {
+                t.waves = w; t.grid_cap = cap; t.ring = ring; t.no_regb = noregb;
+            }
         }
         p = q + 1;
     }
@@ -146,7 +157,39 @@ struct spd_model {
     std::vector<float> rope_host;
     GemmTuning t_qkv, t_o, t_gu, t_down, t_lm;
     int attn_wg_target;
+    // optional tracing: HIP events around every launch group of a forward
+    struct Span { int kind; hipEvent_t a, b; };
+    bool prof_on = false;
+    std::vector<Span> spans;
+    std::vector<hipEvent_t> pool;
+    hipEvent_t take_event() {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+    ~spd_model() {
+        for (auto &sp : spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+        for (auto e : pool) (void)hipEventDestroy(e);
+    }
 };
+
+namespace {
+enum ProfKind { PK_QKV = 0, PK_O, PK_GATE_UP, PK_DOWN, PK_LM_HEAD, PK_ATTENTION, PK_RMSNORM, PK_EMBED, PK_COUNT };
+
+// Runs one launch; when tracing is on, brackets it with events on the same stream.
+#define PROF_TRY(kind, expr)                                                                   \
+    do {                                                                                       \
+        spd_model::Span sp_{(kind), nullptr, nullptr};                                         \
+        if (m->prof_on) {                                                                      \
+            sp_.a = m->take_event(); sp_.b = m->take_event();                                  \
+            if (!sp_.a || !sp_.b) return fail(SPD_ERR_HIP, "hipEventCreate failed");           \
+            HIP_TRY(hipEventRecord(sp_.a, st));                                                \
+        }                                                                                      \
+        HIP_TRY(expr);                                                                         \
+        if (m->prof_on) { HIP_TRY(hipEventRecord(sp_.b, st)); m->spans.push_back(sp_); }       \
+    } while (0)
+}  // namespace
 
 extern "C" {
 
@@ -295,50 +338,62 @@ int32_t forward(spd_model *m, const int32_t *tokens, const float *embeds, int se
     float *qkv = (float *)(m->ws + L.qkv);
     void *xn = m->ws + L.xn, *xo = m->ws + L.xo, *xf = m->ws + L.xf;
 
-    if (tokens) HIP_TRY(launch_embed_gather(m->packed + L.embed, tokens, rows, d, V, h, st));
-    else HIP_TRY(hipMemcpyAsync(h, embeds, (size_t)rows * d * 4, hipMemcpyDeviceToDevice, st));
+    float *ssq_a = (float *)(m->ws + L.ssq_a), *ssq_b = (float *)(m->ws + L.ssq_b);
+    const int d_tiles = d / 16;
+    auto gain_of = [&](size_t off) { return (const float *)(m->packed + off); };
 
-    // key-range split: aim at ~attn_wg_target workgroups, slices of 32..256 keys
+    // input rows -> h, packed (h * attn_norm[0]) and sum of squares (one part per row)
+    PROF_TRY(PK_EMBED, launch_input_rows(m->packed + L.embed, tokens, embeds, rows, d, V, gain_of(L.attn_norm[0]),
+                                         h, xn, ssq_b, st));
+
+    // key-range split: aim at ~attn_wg_target workgroups, slices of 32..128 keys, at most 64 slices
     int want_split = m->attn_wg_target / (n_seqs * c.n_heads);
     if (want_split < 1) want_split = 1;
     int split_len = (max_total + want_split - 1) / want_split;
     split_len = (split_len + 31) / 32 * 32;
     if (split_len < kMinSplit) split_len = kMinSplit;
-    if (split_len > 256) split_len = 256;
+    if ((max_total + split_len - 1) / split_len > 64) split_len = ((max_total + 63) / 64 + 31) / 32 * 32;
+    if (split_len > kMaxSplit) split_len = kMaxSplit;
     at.n_split = (max_total + split_len - 1) / split_len;
     at.split_len = split_len;
     at.qkv = qkv;
     at.rope = (const float *)(m->ws + L.rope);
     at.part_o = (float *)(m->ws + L.part_o);
     at.part_ml = (float *)(m->ws + L.part_ml);
+    at.counters = (int32_t *)(m->ws + L.counters);
     at.xout = xo;
     at.n_seqs = n_seqs; at.M = M; at.H = c.n_heads; at.dh = c.head_dim; at.max_positions = c.max_positions;
 
     for (int l = 0; l < c.n_layers; ++l) {
-        HIP_TRY(launch_rmsnorm_pack(h, (const float *)(m->packed + L.attn_norm[l]), rows, d, c.rms_eps, xn, st));
+        // RMSNorm is folded into the projections: the producer of h (input rows / O / down
+        // epilogue) leaves packed (h * gain) and per-tile sums of squares; the consumer
+        // scales its accumulators by 1 / rms.
         GemmArgs g{};
         g.W = m->packed + L.wqkv[l]; g.X = xn; g.N = 3 * HD; g.K = d; g.rows = rows; g.Y = qkv; g.ldy = 3 * HD;
-        HIP_TRY(launch_gemm(g, EPI_STORE, m->t_qkv, st));
+        g.ssq_in = ssq_b; g.ssq_in_parts = (l == 0) ? 1 : d_tiles; g.eps = c.rms_eps;
+        PROF_TRY(PK_QKV, launch_gemm(g, EPI_STORE, m->t_qkv, st));
         char *kv_l = m->kv + (size_t)l * L.kv_layer_stride + (size_t)seq0 * c.n_heads * c.max_positions * c.head_dim * 2;
         at.k_cache = kv_l;
         at.v_cache = kv_l + L.kv_half;
-        HIP_TRY(launch_attention(at, st));
+        PROF_TRY(PK_ATTENTION, launch_attention(at, st));
         g = GemmArgs{};
         g.W = m->packed + L.wo[l]; g.X = xo; g.N = d; g.K = HD; g.rows = rows; g.Y = h; g.ldy = d;
-        HIP_TRY(launch_gemm(g, EPI_RESIDUAL, m->t_o, st));
-        HIP_TRY(launch_rmsnorm_pack(h, (const float *)(m->packed + L.mlp_norm[l]), rows, d, c.rms_eps, xn, st));
+        g.gain_next = gain_of(L.mlp_norm[l]); g.Xnext = xn; g.ssq_out = ssq_a;
+        PROF_TRY(PK_O, launch_gemm(g, EPI_RESIDUAL, m->t_o, st));
         g = GemmArgs{};
         g.W = m->packed + L.wgu[l]; g.X = xn; g.N = 2 * F; g.K = d; g.rows = rows; g.Xout = xf; g.K_out = F;
-        HIP_TRY(launch_gemm(g, EPI_SWIGLU, m->t_gu, st));
+        g.ssq_in = ssq_a; g.ssq_in_parts = d_tiles; g.eps = c.rms_eps;
+        PROF_TRY(PK_GATE_UP, launch_gemm(g, EPI_SWIGLU, m->t_gu, st));
         g = GemmArgs{};
         g.W = m->packed + L.wdown[l]; g.X = xf; g.N = d; g.K = F; g.rows = rows; g.Y = h; g.ldy = d;
-        HIP_TRY(launch_gemm(g, EPI_RESIDUAL, m->t_down, st));
+        g.gain_next = gain_of(l + 1 < c.n_layers ? L.attn_norm[l + 1] : L.final_norm); g.Xnext = xn; g.ssq_out = ssq_b;
+        PROF_TRY(PK_DOWN, launch_gemm(g, EPI_RESIDUAL, m->t_down, st));
     }
     if (logits_out) {
-        HIP_TRY(launch_rmsnorm_pack(h, (const float *)(m->packed + L.final_norm), rows, d, c.rms_eps, xn, st));
         GemmArgs g{};
         g.W = m->packed + L.lm_head; g.X = xn; g.N = V; g.K = d; g.rows = rows; g.Y = logits_out; g.ldy = V;
-        HIP_TRY(launch_gemm(g, EPI_STORE, m->t_lm, st));
+        g.ssq_in = ssq_b; g.ssq_in_parts = d_tiles; g.eps = c.rms_eps;
+        PROF_TRY(PK_LM_HEAD, launch_gemm(g, EPI_STORE, m->t_lm, st));
     }
     for (int s = 0; s < n_seqs; ++s) m->lens[seq0 + s] += M;
     return SPD_OK;
@@ -368,6 +423,27 @@ int32_t prefill_common(spd_model *m, int32_t seq, const float *embeds, const int
 }  // namespace
 
 extern "C" {
+
+int32_t spd_trace_enable(spd_model *m, int32_t enable) {
+    if (!m) return fail(SPD_ERR_INVALID_ARG, "NULL model");
+    m->prof_on = enable != 0;
+    return SPD_OK;
+}
+
+int32_t spd_trace_read(spd_model *m, int32_t n_kinds, double *ms_sum, int32_t *count) {
+    if (!m || !ms_sum || !count || n_kinds < 1) return fail(SPD_ERR_INVALID_ARG, "bad argument to spd_trace_read");
+    for (int i = 0; i < n_kinds; ++i) { ms_sum[i] = 0.0; count[i] = 0; }
+    for (auto &sp : m->spans) {
+        HIP_TRY(hipEventSynchronize(sp.b));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
+        if (sp.kind < n_kinds) { ms_sum[sp.kind] += ms; count[sp.kind] += 1; }
+        m->pool.push_back(sp.a);
+        m->pool.push_back(sp.b);
+    }
+    m->spans.clear();
+    return SPD_OK;
+}
 
 int32_t spd_prefill(spd_model *m, int32_t seq, const float *embeds, int32_t n_rows, float *last_logits, void *stream) {
     if (!embeds) return fail(SPD_ERR_INVALID_ARG, "NULL embeds");

@@ -1,54 +1,39 @@
-// Row-wise kernels of the decoder forward: embedding gather, RMSNorm fused with the
-// head/tail split that produces the matrix-core B operand, buffer clearing.
+// Row-wise kernels of the decoder forward: the input rows (embedding gather or caller's
+// embedding rows) with the first RMSNorm's operand, and buffer clearing.
 #include "launch.h"
 
 namespace spd {
 
-__global__ void embed_gather_kernel(const uint16_t *__restrict__ E, const int32_t *__restrict__ tokens,
-                                    int d, int vocab, float *__restrict__ h) {
-    int row = blockIdx.x;
-    int tok = min(max(tokens[row], 0), vocab - 1);                    // never read outside the table
-    const uint16_t *src = E + (size_t)tok * d;
-    float *dst = h + (size_t)row * d;
-    for (int k = threadIdx.x * 8; k < d; k += blockDim.x * 8) {      // d % 8 == 0
-        uint4 v = *reinterpret_cast<const uint4 *>(src + k);
-        float4 a = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y)};
-        float4 b = {bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
-        *reinterpret_cast<float4 *>(dst + k) = a;
-        *reinterpret_cast<float4 *>(dst + k + 4) = b;
-    }
-}
-
-hipError_t launch_embed_gather(const void *embed_bf16, const int32_t *tokens, int rows, int d, int vocab,
-                               float *h, hipStream_t stream) {
-    hipLaunchKernelGGL(embed_gather_kernel, dim3(rows), dim3(256), 0, stream,
-                       (const uint16_t *)embed_bf16, tokens, d, vocab, h);
-    return hipGetLastError();
-}
-
-// y = x / sqrt(mean(x^2) + eps) * gain, float32; written as bf16 head + tail in B-operand order.
-__global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *__restrict__ h,
-                                                           const float *__restrict__ gain, int d, float eps,
-                                                           uint16_t *__restrict__ xpack) {
+// One workgroup per input row.  Writes the float32 residual row h, the packed bf16
+// head/tail operand of (h * gain) for the first QKV projection, and sum(h^2) of the row
+// (the RMSNorm scale itself is applied inside that projection).
+__global__ __launch_bounds__(256) void input_rows_kernel(const uint16_t *__restrict__ E,
+                                                         const int32_t *__restrict__ tokens,
+                                                         const float *__restrict__ embeds, int d, int vocab,
+                                                         const float *__restrict__ gain, float *__restrict__ h,
+                                                         uint16_t *__restrict__ xpack, float *__restrict__ ssq) {
     const int row = blockIdx.x;
-    const float *x = h + (size_t)row * d;
-    float ss = 0.f;
-    for (int k = threadIdx.x * 4; k < d; k += 256 * 4) {              // d % 4 == 0
-        float4 v = *reinterpret_cast<const float4 *>(x + k);
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-    __shared__ float part[4];
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
-    __syncthreads();
-    float total = (part[0] + part[1]) + (part[2] + part[3]);
-    float inv = 1.0f / sqrtf(total / (float)d + eps);
     const int KS = d / 32;
-    for (int k = threadIdx.x * 4; k < d; k += 256 * 4) {
-        float4 v = *reinterpret_cast<const float4 *>(x + k);
+    const uint16_t *src_tok = nullptr;
+    if (tokens) {
+        int tok = min(max(tokens[row], 0), vocab - 1);                // never read outside the table
+        src_tok = E + (size_t)tok * d;
+    }
+    const float *src_row = embeds ? embeds + (size_t)row * d : nullptr;
+    float *dst = h + (size_t)row * d;
+    float ss = 0.f;
+    for (int k = threadIdx.x * 4; k < d; k += 256 * 4) {              // d % 32 == 0
+        float4 v;
+        if (src_tok) {
+            uint2 p = *reinterpret_cast<const uint2 *>(src_tok + k);
+            v = float4{bf16_lo(p.x), bf16_hi(p.x), bf16_lo(p.y), bf16_hi(p.y)};
+        } else {
+            v = *reinterpret_cast<const float4 *>(src_row + k);
+        }
+        *reinterpret_cast<float4 *>(dst + k) = v;
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
         float4 g = *reinterpret_cast<const float4 *>(gain + k);
-        float y[4] = {v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w};
+        float y[4] = {v.x * g.x, v.y * g.y, v.z * g.z, v.w * g.w};
         union { uint2 v; uint16_t h[4]; } hi, lo;
 #pragma unroll
         for (int e = 0; e < 4; ++e) split_hi_lo(y[e], hi.h[e], lo.h[e]);
@@ -56,12 +41,20 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(const float *__restri
         *reinterpret_cast<uint2 *>(xpack + xpack_index(row, k, KS, 0)) = hi.v;
         *reinterpret_cast<uint2 *>(xpack + xpack_index(row, k, KS, 1)) = lo.v;
     }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    __shared__ float part[4];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) ssq[row] = (part[0] + part[1]) + (part[2] + part[3]);
 }
 
-hipError_t launch_rmsnorm_pack(const float *h, const float *gain, int rows, int d, float eps,
-                               void *xpack, hipStream_t stream) {
-    hipLaunchKernelGGL(rmsnorm_pack_kernel, dim3(rows), dim3(256), 0, stream, h, gain, d, eps,
-                       (uint16_t *)xpack);
+hipError_t launch_input_rows(const void *embed_bf16, const int32_t *tokens, const float *embeds, int rows,
+                             int d, int vocab, const float *gain, float *h, void *xpack, float *ssq,
+                             hipStream_t stream) {
+    if ((!tokens) == (!embeds)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(input_rows_kernel, dim3(rows), dim3(256), 0, stream, (const uint16_t *)embed_bf16,
+                       tokens, embeds, d, vocab, gain, h, (uint16_t *)xpack, ssq);
     return hipGetLastError();
 }
 

@@ -24,7 +24,8 @@ SPD_MAX_ROWS, SPD_MAX_M = 64, 8
 
 EXPORTS = ["spd_last_error", "spd_model_bytes", "spd_model_create", "spd_model_destroy", "spd_kv_set_len",
            "spd_kv_get_len", "spd_prefill", "spd_prefill_tokens", "spd_verify_forward", "spd_draft_step",
-           "spd_accept_workspace_bytes", "spd_speculative_accept"]
+           "spd_accept_workspace_bytes", "spd_speculative_accept", "spd_trace_enable", "spd_trace_read"]
+TRACE_KINDS = ["qkv", "o", "gate_up", "down", "lm_head", "attention", "rmsnorm", "embed"]
 
 
 class SpdError(RuntimeError):
@@ -66,6 +67,8 @@ _lib.spd_verify_forward.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp]
 _lib.spd_draft_step.argtypes = [_vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp, _vp]
 _lib.spd_accept_workspace_bytes.argtypes = [_i32, _i32, _i32, _szp]
 _lib.spd_speculative_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _u32, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.spd_trace_enable.argtypes = [_vp, _i32]
+_lib.spd_trace_read.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i32)]
 for _name in EXPORTS:
     if _name != "spd_last_error":
         getattr(_lib, _name).restype = _i32
@@ -174,6 +177,18 @@ class Model:
         _check(_lib.spd_draft_step(self.handle, _ptr(tokens_in, torch.int32), n_seqs, n_in, float(temperature),
                                    _ptr(u_draft, torch.float32), _ptr(D_row_out, torch.float32),
                                    _ptr(token_out, torch.int32), _stream()))
+
+
+    def spd_trace_enable(self, enable):
+        _check(_lib.spd_trace_enable(self.handle, int(bool(enable))))
+
+    def spd_trace_read(self):
+        """{kind: (milliseconds summed over launches, launches)} since the last read; waits for the events."""
+        n = len(TRACE_KINDS)
+        ms = (ctypes.c_double * n)()
+        cnt = (ctypes.c_int32 * n)()
+        _check(_lib.spd_trace_read(self.handle, n, ms, cnt))
+        return {k: (ms[i], cnt[i]) for i, k in enumerate(TRACE_KINDS)}
 
 
 def spd_accept_workspace_bytes(n_seqs, gamma, vocab):
