@@ -56,12 +56,10 @@ hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t stream);
 struct AttnArgs {
     const float *qkv;        // [rows, 3 * H * dh] (q | k | v), before RoPE
     const float *rope;       // [max_positions, dh / 2, 2] (cos, sin)
-    void *k_cache, *v_cache; // this layer: bf16 [max_seqs, H, max_positions, dh]
-    float *part_o;           // [n_seqs, H, n_split, 8, dh]
-    float *part_ml;          // [n_seqs, H, n_split, 8, 2]  (max, sum)
+    void *k_cache;           // this layer: bf16 [max_seqs, H, max_positions, dh]   (K after RoPE)
+    void *v_cache;           // this layer: bf16 [max_seqs, H, dh, v_stride]        (V transposed)
     void *xout;              // packed activations, K = H * dh (attention output)
-    int32_t *counters;       // [n_seqs * H] zero between launches (last-arriving slice merges)
-    int n_seqs, M, H, dh, max_positions, n_split, split_len;
+    int n_seqs, M, H, dh, max_positions, v_stride;
     SeqLens lens;            // KV length of every sequence before this call
 };
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream);

@@ -39,8 +39,6 @@ int32_t fail(int32_t code, const char *fmt, ...) {
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-constexpr int kMinSplit = 32;      // smallest key-slice length the attention launch uses
-constexpr int kMaxSplit = 128;     // largest; with at most 64 slices this bounds max_positions at 8192
 
 struct Layout {                    // byte offsets inside the three buffers
     // packed
@@ -48,10 +46,10 @@ struct Layout {                    // byte offsets inside the three buffers
     std::vector<size_t> attn_norm, wqkv, wo, mlp_norm, wgu, wdown;
     size_t packed_total;
     // kv
-    size_t kv_layer_stride, kv_half, kv_total;
+    size_t kv_layer_stride, kv_k_bytes, kv_v_bytes, kv_total;
+    int v_stride;
     // workspace
-    size_t h, qkv, xn, xo, xf, part_o, part_ml, rope, logits, ssq_a, ssq_b, counters, ws_total;
-    int n_split_max;
+    size_t h, qkv, xn, xo, xf, rope, logits, ssq_a, ssq_b, ws_total;
 };
 
 int32_t check_shape(const spd_model_config &c) {
@@ -66,7 +64,6 @@ int32_t check_shape(const spd_model_config &c) {
     if (c.d_ffn % 8) return fail(SPD_ERR_SHAPE, "d_ffn %d must be a multiple of 8", c.d_ffn);
     if (c.vocab % 16) return fail(SPD_ERR_SHAPE, "vocab %d must be a multiple of 16", c.vocab);
     if (c.max_seqs > SPD_MAX_ROWS) return fail(SPD_ERR_SHAPE, "max_seqs %d exceeds %d", c.max_seqs, SPD_MAX_ROWS);
-    if (c.max_positions > 64 * kMaxSplit) return fail(SPD_ERR_SHAPE, "max_positions %d exceeds %d", c.max_positions, 64 * kMaxSplit);
     if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return fail(SPD_ERR_SHAPE, "bad rms_eps / rope_theta");
     return SPD_OK;
 }
@@ -88,25 +85,23 @@ void make_layout(const spd_model_config &c, Layout &L) {
     }
     L.packed_total = off;
 
-    L.kv_half = (size_t)c.max_seqs * c.n_heads * c.max_positions * c.head_dim * 2;   // K or V of a layer
-    L.kv_layer_stride = 2 * L.kv_half;
+    L.v_stride = (c.max_positions + 31) / 32 * 32;         // V is stored transposed, rows padded to 32 positions
+    L.kv_k_bytes = (size_t)c.max_seqs * c.n_heads * c.max_positions * c.head_dim * 2;
+    L.kv_v_bytes = (size_t)c.max_seqs * c.n_heads * c.head_dim * L.v_stride * 2;
+    L.kv_layer_stride = align_up(L.kv_k_bytes, 256) + align_up(L.kv_v_bytes, 256);
     L.kv_total = L.kv_layer_stride * c.n_layers;
 
     off = 0;
-    L.n_split_max = (c.max_positions + kMinSplit - 1) / kMinSplit;
     const size_t KSd = d / 32, KShd = HD / 32, KSf = (F + 31) / 32;
     L.h = take((size_t)kMaxRows * d * 4);
     L.qkv = take((size_t)kMaxRows * 3 * HD * 4);
     L.xn = take((size_t)kMaxGroups * KSd * 1024);
     L.xo = take((size_t)kMaxGroups * KShd * 1024);
     L.xf = take((size_t)kMaxGroups * KSf * 1024);
-    L.part_o = take((size_t)c.max_seqs * c.n_heads * L.n_split_max * 8 * c.head_dim * 4);
-    L.part_ml = take((size_t)c.max_seqs * c.n_heads * L.n_split_max * 8 * 2 * 4);
     L.rope = take((size_t)c.max_positions * (c.head_dim / 2) * 2 * 4);
     L.logits = take((size_t)kMaxRows * V * 4);
     L.ssq_a = take((size_t)(d / 16) * kMaxRows * 4);
     L.ssq_b = take((size_t)(d / 16) * kMaxRows * 4);
-    L.counters = take((size_t)c.max_seqs * c.n_heads * 4);
     L.ws_total = off;
 }
 
@@ -156,7 +151,6 @@ struct spd_model {
     std::vector<int32_t> lens;
     std::vector<float> rope_host;
     GemmTuning t_qkv, t_o, t_gu, t_down, t_lm;
-    int attn_wg_target;
     // optional tracing: HIP events around every launch group of a forward
     struct Span { int kind; hipEvent_t a, b; };
     bool prof_on = false;
@@ -262,8 +256,11 @@ int32_t spd_model_create(const spd_model_config *cfg, const spd_weights *w, void
         CREATE_TRY(launch_pack_weight(w->w_gate[l], w->w_up[l], nullptr, PACK_GATE_UP, 2 * F, d, m->packed + L.wgu[l], st));
         CREATE_TRY(launch_pack_weight(w->w_down[l], nullptr, nullptr, PACK_PLAIN, d, F, m->packed + L.wdown[l], st));
     }
-    // workspace starts cleared: the padding columns of the packed activation buffers must be zero
+    // workspace starts cleared: the padding columns of the packed activation buffers must be zero;
+    // the KV cache too: the attention kernel reads (and masks) whole 32-position units, so every
+    // slot must hold a finite value
     CREATE_TRY(launch_fill_zero(m->ws, L.ws_total, st));
+    CREATE_TRY(launch_fill_zero(m->kv, L.kv_total, st));
     // RoPE table: angle(pos, i) = pos * theta^(-2i/head_dim), computed in double
     const int half = cfg->head_dim / 2;
     m->rope_host.resize((size_t)cfg->max_positions * half * 2);
@@ -281,8 +278,6 @@ int32_t spd_model_create(const spd_model_config *cfg, const spd_weights *w, void
     m->t_gu = default_tuning(2 * F, d);     env_tuning("gu", m->t_gu);
     m->t_down = default_tuning(d, F);       env_tuning("down", m->t_down);
     m->t_lm = default_tuning(V, d);         env_tuning("lm", m->t_lm);
-    m->attn_wg_target = 512;
-    if (const char *e = getenv("SPD_ATTN_WGS")) m->attn_wg_target = atoi(e) > 0 ? atoi(e) : 512;
     *out = m;
     return SPD_OK;
 }
@@ -346,23 +341,11 @@ int32_t forward(spd_model *m, const int32_t *tokens, const float *embeds, int se
     PROF_TRY(PK_EMBED, launch_input_rows(m->packed + L.embed, tokens, embeds, rows, d, V, gain_of(L.attn_norm[0]),
                                          h, xn, ssq_b, st));
 
-    // key-range split: aim at ~attn_wg_target workgroups, slices of 32..128 keys, at most 64 slices
-    int want_split = m->attn_wg_target / (n_seqs * c.n_heads);
-    if (want_split < 1) want_split = 1;
-    int split_len = (max_total + want_split - 1) / want_split;
-    split_len = (split_len + 31) / 32 * 32;
-    if (split_len < kMinSplit) split_len = kMinSplit;
-    if ((max_total + split_len - 1) / split_len > 64) split_len = ((max_total + 63) / 64 + 31) / 32 * 32;
-    if (split_len > kMaxSplit) split_len = kMaxSplit;
-    at.n_split = (max_total + split_len - 1) / split_len;
-    at.split_len = split_len;
     at.qkv = qkv;
     at.rope = (const float *)(m->ws + L.rope);
-    at.part_o = (float *)(m->ws + L.part_o);
-    at.part_ml = (float *)(m->ws + L.part_ml);
-    at.counters = (int32_t *)(m->ws + L.counters);
     at.xout = xo;
     at.n_seqs = n_seqs; at.M = M; at.H = c.n_heads; at.dh = c.head_dim; at.max_positions = c.max_positions;
+    at.v_stride = L.v_stride;
 
     for (int l = 0; l < c.n_layers; ++l) {
         // RMSNorm is folded into the projections: the producer of h (input rows / O / down
@@ -372,9 +355,9 @@ int32_t forward(spd_model *m, const int32_t *tokens, const float *embeds, int se
         g.W = m->packed + L.wqkv[l]; g.X = xn; g.N = 3 * HD; g.K = d; g.rows = rows; g.Y = qkv; g.ldy = 3 * HD;
         g.ssq_in = ssq_b; g.ssq_in_parts = (l == 0) ? 1 : d_tiles; g.eps = c.rms_eps;
         PROF_TRY(PK_QKV, launch_gemm(g, EPI_STORE, m->t_qkv, st));
-        char *kv_l = m->kv + (size_t)l * L.kv_layer_stride + (size_t)seq0 * c.n_heads * c.max_positions * c.head_dim * 2;
-        at.k_cache = kv_l;
-        at.v_cache = kv_l + L.kv_half;
+        char *kv_l = m->kv + (size_t)l * L.kv_layer_stride;
+        at.k_cache = kv_l + (size_t)seq0 * c.n_heads * c.max_positions * c.head_dim * 2;
+        at.v_cache = kv_l + align_up(L.kv_k_bytes, 256) + (size_t)seq0 * c.n_heads * c.head_dim * L.v_stride * 2;
         PROF_TRY(PK_ATTENTION, launch_attention(at, st));
         g = GemmArgs{};
         g.W = m->packed + L.wo[l]; g.X = xo; g.N = d; g.K = HD; g.rows = rows; g.Y = h; g.ldy = d;
