@@ -28,8 +28,8 @@
  *   - The library allocates no device memory: weights (packed), KV cache and
  *     workspace live in caller-owned buffers whose sizes spd_model_bytes()
  *     reports.  The model borrows them until spd_model_destroy().
- *   - Shapes: d_model % 32 == 0, head_dim in {64, 128}, (n_heads*head_dim) % 16
- *     == 0, d_ffn % 8 == 0, vocab % 16 == 0, max_positions <= 8192, rows per call
+ *   - Shapes: d_model % 32 == 0, head_dim in {64, 128}, (n_heads*head_dim) % 32
+ *     == 0, d_ffn % 8 == 0, vocab % 16 == 0, max_seqs <= 64, rows per call
  *     (n_seqs * M) <= 64, M <= 8.  Violations return SPD_ERR_SHAPE before anything is launched.
  */
 #ifndef SPD_H
@@ -188,12 +188,19 @@ int32_t spd_speculative_accept(const float *target, const float *draft, const in
  * the recorded events (the one call here that blocks the host), adds the elapsed
  * milliseconds and launch counts per kind into h_ms_sum[n_kinds] / h_count[n_kinds] and
  * forgets them.  Kinds: 0 QKV projection, 1 O projection, 2 gate|up projection + SwiGLU,
- * 3 down projection, 4 LM head, 5 RoPE + KV append + attention, 6 unused (RMSNorm is
- * folded into the projections), 7 input rows (embedding gather).  The events perturb the stream slightly: time whole
+ * 3 down projection, 4 LM head, 5 RoPE + KV append + attention, 6 the whole forward as one
+ * persistent kernel (calls of up to 8 rows; kinds 0-5 and 7 then stay empty), 7 input rows
+ * (embedding gather).  The events perturb the stream slightly: time whole
  * steps with tracing off. */
 #define SPD_TRACE_KINDS 8
 int32_t spd_trace_enable(spd_model *model, int32_t enable);
 int32_t spd_trace_read(spd_model *model, int32_t n_kinds, double *h_ms_sum, int32_t *h_count);
+/* Stage timeline of the LAST whole-forward kernel launched while tracing was enabled, as seen
+ * by workgroup 0: for each stage (input rows; per layer QKV, attention, O, gate|up, down; LM
+ * head) the microseconds it spent working and then waiting at the device-wide barrier.
+ * Blocks the host (synchronous copy).  h_us_work / h_us_wait: [max_stages]. */
+int32_t spd_trace_stages(spd_model *model, int32_t max_stages, double *h_us_work, double *h_us_wait,
+                         int32_t *h_n_stages);
 
 #ifdef __cplusplus
 }

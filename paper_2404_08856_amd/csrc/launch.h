@@ -64,6 +64,35 @@ struct AttnArgs {
 };
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream);
 
+// ---- whole forward in one persistent kernel (rows <= 8) -------------------------------------
+struct MegaArgs {
+    // model
+    const char *packed;                       // packed weights (spd_model_create layout)
+    size_t off_embed, off_lm_head, off_final_norm;
+    size_t off_attn_norm0, off_wqkv0, off_wo0, off_mlp_norm0, off_wgu0, off_wdown0, layer_stride;
+    char *kv;                                 // KV cache: per layer K [seqs][H][pos][dh] then V^T [seqs][H][dh][v_stride]
+    size_t kv_layer_stride, kv_v_offset;
+    int n_layers, d, H, dh, F, V, max_positions, v_stride;
+    float eps;
+    const float *rope;
+    // workspace: float32 row-major arrays of 8 rows, exchanged between workgroups
+    float *h, *hg, *qkv, *att, *xf, *ssq_a, *ssq_b;    // ssq_*: [d / 16][8]
+    unsigned *bar;                            // arrival counter of the device-wide barrier (only grows)
+    int *abort_flag;                          // set if a barrier wait hit its spin limit
+    unsigned long long *stage_clock;          // NULL, or [2 * (barriers + 1)] wall-clock stamps of workgroup 0
+    // this call
+    const int32_t *tokens;                    // [rows] or NULL
+    const float *embeds;                      // [rows][d] or NULL
+    float *logits;                            // [rows][V] or NULL (skip the LM head)
+    int n_seqs, M, rows, seq0;
+    unsigned bar_base;                        // counter value before this launch
+    SeqLens lens;
+};
+// grid = number of CUs (one resident workgroup each); cooperative launch
+hipError_t launch_megakernel(const MegaArgs &a, int grid, hipStream_t stream);
+int megakernel_max_grid(int dh);              // 0 if the kernel cannot be made resident
+constexpr int kMegaBarriersPerLayer = 5;
+
 // ---- sampling ---------------------------------------------------------------------
 struct AcceptArgs {
     const float *target, *draft;

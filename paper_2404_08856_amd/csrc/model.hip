@@ -50,6 +50,7 @@ struct Layout {                    // byte offsets inside the three buffers
     int v_stride;
     // workspace
     size_t h, qkv, xn, xo, xf, rope, logits, ssq_a, ssq_b, ws_total;
+    size_t m_hg, m_att, m_xf, m_ssq_a, m_ssq_b, m_sync, m_clock;     // arrays of the whole-forward kernel (8 rows)
 };
 
 int32_t check_shape(const spd_model_config &c) {
@@ -102,6 +103,13 @@ void make_layout(const spd_model_config &c, Layout &L) {
     L.logits = take((size_t)kMaxRows * V * 4);
     L.ssq_a = take((size_t)(d / 16) * kMaxRows * 4);
     L.ssq_b = take((size_t)(d / 16) * kMaxRows * 4);
+    L.m_hg = take((size_t)8 * d * 4);
+    L.m_att = take((size_t)8 * HD * 4);
+    L.m_xf = take((size_t)8 * KSf * 32 * 4);
+    L.m_ssq_a = take((size_t)(d / 16) * 8 * 4);
+    L.m_ssq_b = take((size_t)(d / 16) * 8 * 4);
+    L.m_sync = take(256);
+    L.m_clock = take((size_t)(2 * (2 + kMegaBarriersPerLayer * c.n_layers)) * 8);
     L.ws_total = off;
 }
 
@@ -151,6 +159,8 @@ struct spd_model {
     std::vector<int32_t> lens;
     std::vector<float> rope_host;
     GemmTuning t_qkv, t_o, t_gu, t_down, t_lm;
+    int mega_grid = 0;                 // workgroups of the whole-forward kernel (0: not available)
+    unsigned bar_count = 0;            // value of the device-wide barrier counter after the last launch
     // optional tracing: HIP events around every launch group of a forward
     struct Span { int kind; hipEvent_t a, b; };
     bool prof_on = false;
@@ -169,7 +179,7 @@ struct spd_model {
 };
 
 namespace {
-enum ProfKind { PK_QKV = 0, PK_O, PK_GATE_UP, PK_DOWN, PK_LM_HEAD, PK_ATTENTION, PK_RMSNORM, PK_EMBED, PK_COUNT };
+enum ProfKind { PK_QKV = 0, PK_O, PK_GATE_UP, PK_DOWN, PK_LM_HEAD, PK_ATTENTION, PK_FORWARD, PK_EMBED, PK_COUNT };
 
 // Runs one launch; when tracing is on, brackets it with events on the same stream.
 #define PROF_TRY(kind, expr)                                                                   \
@@ -278,6 +288,12 @@ int32_t spd_model_create(const spd_model_config *cfg, const spd_weights *w, void
     m->t_gu = default_tuning(2 * F, d);     env_tuning("gu", m->t_gu);
     m->t_down = default_tuning(d, F);       env_tuning("down", m->t_down);
     m->t_lm = default_tuning(V, d);         env_tuning("lm", m->t_lm);
+    // Whole-forward persistent kernel for calls of up to 8 rows.  Opt-in (SPD_MEGA=1): at the 7B
+    // shape its device-wide barriers and lock-step stages currently cost more than the launch
+    // gaps of the per-stage kernels they remove, so the per-stage path is the default.
+    m->mega_grid = 0;
+    if (getenv("SPD_MEGA") && cfg->n_layers > 0) m->mega_grid = megakernel_max_grid(cfg->head_dim);
+    if (const char *e = getenv("SPD_MEGA_GRID")) { int g = atoi(e); if (g > 0 && g < m->mega_grid) m->mega_grid = g; }
     *out = m;
     return SPD_OK;
 }
@@ -329,6 +345,31 @@ int32_t forward(spd_model *m, const int32_t *tokens, const float *embeds, int se
         if (len + M > max_total) max_total = len + M;
     }
     const int d = c.d_model, HD = c.n_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
+    if (rows <= 8 && m->mega_grid > 0) {
+        MegaArgs ma{};
+        ma.packed = m->packed;
+        ma.off_embed = L.embed; ma.off_lm_head = L.lm_head; ma.off_final_norm = L.final_norm;
+        ma.off_attn_norm0 = L.attn_norm[0]; ma.off_wqkv0 = L.wqkv[0]; ma.off_wo0 = L.wo[0];
+        ma.off_mlp_norm0 = L.mlp_norm[0]; ma.off_wgu0 = L.wgu[0]; ma.off_wdown0 = L.wdown[0];
+        ma.layer_stride = c.n_layers > 1 ? L.attn_norm[1] - L.attn_norm[0] : 0;
+        ma.kv = m->kv; ma.kv_layer_stride = L.kv_layer_stride; ma.kv_v_offset = align_up(L.kv_k_bytes, 256);
+        ma.n_layers = c.n_layers; ma.d = d; ma.H = c.n_heads; ma.dh = c.head_dim; ma.F = F; ma.V = V;
+        ma.max_positions = c.max_positions; ma.v_stride = L.v_stride; ma.eps = c.rms_eps;
+        ma.rope = (const float *)(m->ws + L.rope);
+        ma.h = (float *)(m->ws + L.h); ma.hg = (float *)(m->ws + L.m_hg); ma.qkv = (float *)(m->ws + L.qkv);
+        ma.att = (float *)(m->ws + L.m_att); ma.xf = (float *)(m->ws + L.m_xf);
+        ma.ssq_a = (float *)(m->ws + L.m_ssq_a); ma.ssq_b = (float *)(m->ws + L.m_ssq_b);
+        ma.bar = (unsigned *)(m->ws + L.m_sync); ma.abort_flag = (int *)(m->ws + L.m_sync + 64);
+        ma.tokens = tokens; ma.embeds = embeds; ma.logits = logits_out;
+        ma.n_seqs = n_seqs; ma.M = M; ma.rows = rows; ma.seq0 = seq0;
+        ma.bar_base = m->bar_count;
+        ma.stage_clock = m->prof_on ? (unsigned long long *)(m->ws + L.m_clock) : nullptr;
+        ma.lens = at.lens;
+        PROF_TRY(PK_FORWARD, launch_megakernel(ma, m->mega_grid, st));
+        m->bar_count += (unsigned)m->mega_grid * (unsigned)(1 + kMegaBarriersPerLayer * c.n_layers);
+        for (int s = 0; s < n_seqs; ++s) m->lens[seq0 + s] += M;
+        return SPD_OK;
+    }
     float *h = (float *)(m->ws + L.h);
     float *qkv = (float *)(m->ws + L.qkv);
     void *xn = m->ws + L.xn, *xo = m->ws + L.xo, *xf = m->ws + L.xf;
@@ -425,6 +466,21 @@ int32_t spd_trace_read(spd_model *m, int32_t n_kinds, double *ms_sum, int32_t *c
         m->pool.push_back(sp.b);
     }
     m->spans.clear();
+    return SPD_OK;
+}
+
+int32_t spd_trace_stages(spd_model *m, int32_t max_stages, double *us_work, double *us_wait, int32_t *n_stages) {
+    if (!m || !us_work || !us_wait || !n_stages || max_stages < 1) return fail(SPD_ERR_INVALID_ARG, "bad argument to spd_trace_stages");
+    const int n = 1 + kMegaBarriersPerLayer * m->cfg.n_layers + 1;          // stages separated by the barriers
+    std::vector<unsigned long long> clk((size_t)2 * (n + 1));
+    HIP_TRY(hipMemcpy(clk.data(), m->ws + m->L.m_clock, clk.size() * 8, hipMemcpyDeviceToHost));   // blocks
+    *n_stages = n < max_stages ? n : max_stages;
+    for (int i = 0; i < *n_stages; ++i) {
+        // stamps: [2 i + 1] = stage i starts (left barrier i), [2 i] = its work is done (arrives at
+        // barrier i + 1), [2 (i + 1) + 1] = left barrier i + 1
+        us_work[i] = (double)(clk[2 * i] - clk[2 * i + 1]) * 0.01;
+        us_wait[i] = (i + 1 < n) ? (double)(clk[2 * (i + 1) + 1] - clk[2 * i]) * 0.01 : 0.0;
+    }
     return SPD_OK;
 }
 

@@ -24,8 +24,9 @@ SPD_MAX_ROWS, SPD_MAX_M = 64, 8
 
 EXPORTS = ["spd_last_error", "spd_model_bytes", "spd_model_create", "spd_model_destroy", "spd_kv_set_len",
            "spd_kv_get_len", "spd_prefill", "spd_prefill_tokens", "spd_verify_forward", "spd_draft_step",
-           "spd_accept_workspace_bytes", "spd_speculative_accept", "spd_trace_enable", "spd_trace_read"]
-TRACE_KINDS = ["qkv", "o", "gate_up", "down", "lm_head", "attention", "rmsnorm", "embed"]
+           "spd_accept_workspace_bytes", "spd_speculative_accept", "spd_trace_enable", "spd_trace_read",
+           "spd_trace_stages"]
+TRACE_KINDS = ["qkv", "o", "gate_up", "down", "lm_head", "attention", "forward", "embed"]
 
 
 class SpdError(RuntimeError):
@@ -69,6 +70,7 @@ _lib.spd_accept_workspace_bytes.argtypes = [_i32, _i32, _i32, _szp]
 _lib.spd_speculative_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _u32, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.spd_trace_enable.argtypes = [_vp, _i32]
 _lib.spd_trace_read.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i32)]
+_lib.spd_trace_stages.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i32)]
 for _name in EXPORTS:
     if _name != "spd_last_error":
         getattr(_lib, _name).restype = _i32
@@ -181,6 +183,14 @@ class Model:
 
     def spd_trace_enable(self, enable):
         _check(_lib.spd_trace_enable(self.handle, int(bool(enable))))
+
+    def spd_trace_stages(self, max_stages=4096):
+        """[(us working, us waiting at the barrier)] per stage of the last traced whole-forward kernel."""
+        work = (ctypes.c_double * max_stages)()
+        wait = (ctypes.c_double * max_stages)()
+        n = ctypes.c_int32()
+        _check(_lib.spd_trace_stages(self.handle, max_stages, work, wait, ctypes.byref(n)))
+        return [(work[i], wait[i]) for i in range(n.value)]
 
     def spd_trace_read(self):
         """{kind: (milliseconds summed over launches, launches)} since the last read; waits for the events."""

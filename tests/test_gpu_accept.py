@@ -73,12 +73,12 @@ def test_accept_logits_mode_matches_up_to_near_ties():
         ks, ys = ss.speculative_accept(T[s], D[s], d[s], u[s])
         if (int(k[s]), int(y[s])) != (ks, ys):
             mismatches += 1
-            # only legitimate at a near-tie of an accept test or of the inverse-CDF threshold
+            # only legitimate at a near-tie: of an accept test (k differs), or of the inverse-CDF
+            # threshold (same k, the neighbouring token of the cumulative sum)
             margins = [abs(float(u[s, j]) * float(D[s, j, d[s, j]]) - float(T[s, j, d[s, j]])) /
                        max(float(T[s, j, d[s, j]]), 1e-30) for j in range(gamma)]
-            near_accept_tie = min(margins) < 1e-4
-            near_cdf_tie = abs(int(y[s]) - ys) <= 1 or True
-            assert near_accept_tie or near_cdf_tie
+            if int(k[s]) != ks:
+                assert min(margins) < 1e-4, (s, margins)
     assert mismatches <= 2, mismatches
     ap_ref = np.array([[ss.accept_probability(T[s, j, d[s, j]], D[s, j, d[s, j]]) for j in range(gamma)]
                        for s in range(n_seqs)])

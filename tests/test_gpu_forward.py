@@ -183,3 +183,16 @@ def test_verify_is_deterministic_run_to_run():
         outs.append(out.cpu())
     assert torch.equal(outs[0], outs[1])
     model.close()
+
+
+@pytest.mark.parametrize("case", ["tiny", "draft", "7b2"])
+def test_whole_forward_persistent_kernel_opt_in(case, monkeypatch):
+    """The single-launch persistent kernel for calls of up to 8 rows (opt-in through the
+    environment at model creation) computes the same forward."""
+    monkeypatch.setenv("SPD_MEGA", "1")
+    if case == "tiny":
+        run_case(synth.SHAPES["tiny_target"], 32, 32, 5, seed=31, extra_steps=1)
+    elif case == "draft":
+        run_case(synth.SHAPES["tiny_draft"], 0, 65, 1, seed=32, extra_steps=2)
+    else:
+        run_case(synth.llama7b_layers(2), 576, 64, 5, seed=33)
