@@ -20,6 +20,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+# HBM bytes per launch of the gate|up projection kernel at the 7B shape, from the two
+# rocprofv3 --pmc runs summarised in profiles/verify_step_llama7b_hbm_traffic.txt
+# (FETCH_SIZE 88735.0 KiB x 2.0 + WRITE_SIZE 283.9 KiB x 1.0; factors from a 1 GiB copy)
+GATE_UP_7B_TRAFFIC_BYTES = int((88735.0 * 2.0 + 283.9) * 1024)
 
 
 def parse():
@@ -32,8 +36,11 @@ def parse():
     ap.add_argument("--text-tokens", type=int, default=64)
     ap.add_argument("--layers", type=int, default=0, help="development only: fewer layers than the 7B shape (line is marked invalid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-layers", type=int, default=4, help="layers of the oracle's verify step that are timed")
+    ap.add_argument("--cpu-layers", type=int, default=8, help="layers of the oracle's verify step that are timed")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calib-copy", type=int, default=0,
+                    help="after the timed region, run this many plain 1 GiB device copies (reference dispatches of known "
+                         "size for scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -58,12 +65,12 @@ def cpu_baseline(shape, w_host, n_prefix, M, seed):
     cache.v[:, :n_prefix] = rng.standard_normal(cache.v[:, :n_prefix].shape)
     toks = synth.text_tokens(M, sub.vocab, seed + 2)
     times = []
-    for rep in range(3):
+    for rep in range(5):
         cache.length = n_prefix
         t0 = time.perf_counter()
         dec.forward_tokens(cfg, w, cache, toks)
         times.append(time.perf_counter() - t0)
-    t_sub = sorted(times)[1]
+    t_sub = sorted(times)[2]
     # split the measured time into per-layer and head parts by their parameter counts
     per_layer = 4 * sub.d_model ** 2 + 3 * sub.d_model * sub.d_ffn
     head = sub.vocab * sub.d_model
@@ -72,7 +79,7 @@ def cpu_baseline(shape, w_host, n_prefix, M, seed):
     t_full = t_layer * shape.n_layers + t_head
     return {"value": M / t_full, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"oracle verify step (float64 numpy) on {sub.n_layers} of {shape.n_layers} layers + LM head, "
-                      f"{M} rows against {n_prefix} cached positions, median of 3; extrapolated by parameter count "
+                      f"{M} rows against {n_prefix} cached positions, median of 5; extrapolated by parameter count "
                       f"to the full model: {t_full * 1e3:.0f} ms/step"}
 
 
@@ -184,9 +191,16 @@ def main():
         "hbm_GBps": gbps, "hbm_frac_of_peak": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_step": step_bytes,
         "roofline": {"bound": "hbm", "kernel": dom_name,
                      "achieved": dom_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": dom_gbps / HBM_PEAK_GBPS,
-                     "traffic": None, "bytes_per_launch": dom_bytes, "ms_per_launch": dom_ms},
+                     "traffic": GATE_UP_7B_TRAFFIC_BYTES if (dom == "gate_up" and args.layers <= 0) else None,
+                     "bytes_per_launch": dom_bytes, "ms_per_launch": dom_ms},
         "kernels": kinds,
     }
+    if args.calib_copy > 0:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(args.calib_copy):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if args.layers > 0:
         out["invalid"] = "development run with fewer layers than the 7B shape"
     if not args.no_cpu_baseline:
