@@ -36,6 +36,7 @@ def parse():
     ap.add_argument("--text-tokens", type=int, default=64)
     ap.add_argument("--layers", type=int, default=0, help="development only: fewer layers than the 7B shape (line is marked invalid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-side-configs", action="store_true", help="skip the draft-step and accept-kernel timings")
     ap.add_argument("--cpu-layers", type=int, default=8, help="layers of the oracle's verify step that are timed")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calib-copy", type=int, default=0,
@@ -81,6 +82,71 @@ def cpu_baseline(shape, w_host, n_prefix, M, seed):
             "sample": f"oracle verify step (float64 numpy) on {sub.n_layers} of {shape.n_layers} layers + LM head, "
                       f"{M} rows against {n_prefix} cached positions, median of 5; extrapolated by parameter count "
                       f"to the full model: {t_full * 1e3:.0f} ms/step"}
+
+
+def side_configs(args, spd, synth, torch):
+    """The two small single-GPU configurations, timed after the headline region (not part of `value`):
+    the ~110M draft's sequential decode steps and the accept / resample kernels alone."""
+    import numpy as np
+    res = {}
+    # draft alone: 12 layers, d 768, tied embeddings; 64-token prefix; gamma = 4 sequential single-token steps
+    ds = synth.SHAPES["draft_110m"]
+    dm = spd.Model(spd.make_config(ds, 1, 128), synth.make_weights(ds, args.seed + 7, device="cuda"))
+    dm.spd_prefill_tokens(0, torch.from_numpy(synth.text_tokens(64, ds.vocab, args.seed + 7)).cuda())
+    D = torch.empty((1, ds.vocab), dtype=torch.float32, device="cuda")
+    tok = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    ud = torch.from_numpy(synth.uniforms((args.gamma,), args.seed + 8)).cuda()
+
+    def draft_block():
+        dm.spd_kv_set_len([64])
+        for j in range(args.gamma):                 # the sampled token feeds the next step on the device
+            dm.spd_draft_step(tok.view(1, 1), 1.0, ud[j:j + 1], D, tok)
+
+    for _ in range(5):
+        draft_block()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 50
+    e0.record()
+    for _ in range(reps):
+        draft_block()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * args.gamma)
+    dbytes = ds.streamed_weight_bytes() + ds.n_layers * 2 * 66 * ds.n_heads * ds.head_dim * 2
+    res["draft_step"] = {"workload": "draft_110m: 12 layers d=768 12x64 heads ffn 2048 vocab 32000 tied, 64-token prefix, "
+                                     f"{args.gamma} sequential single-token steps incl. softmax + sampling, batch 1",
+                         "us_per_step": us, "algorithmic_bytes_per_step": dbytes, "GBps": dbytes / (us * 1e-6) / 1e9,
+                         "note": "weights (219 MB) stay in the 256 MB memory-side cache between steps"}
+    dm.close()
+    # accept / resample alone: 64 sequences x (gamma + 1) rows x 32000 logits
+    n_seqs, V = 64, 32000
+    per_sigma = {}
+    for sigma in (0.5, 1.0, 2.0):
+        lt, ld = synth.accept_workload(n_seqs, args.gamma, V, sigma, seed=args.seed + 9)
+        lt, ld = torch.from_numpy(lt).cuda(), torch.from_numpy(ld).cuda()
+        g = torch.Generator(device="cuda").manual_seed(args.seed + 10)
+        dtok = torch.multinomial(torch.softmax(ld.reshape(-1, V), -1), 1, generator=g).to(torch.int32).reshape(n_seqs, args.gamma)
+        u = torch.from_numpy(synth.uniforms((n_seqs, args.gamma + 1), args.seed + 11)).cuda()
+        k = torch.empty(n_seqs, dtype=torch.int32, device="cuda")
+        y = torch.empty(n_seqs, dtype=torch.int32, device="cuda")
+        ws = torch.empty(spd.spd_accept_workspace_bytes(n_seqs, args.gamma, V), dtype=torch.uint8, device="cuda")
+        for _ in range(5):
+            spd.spd_speculative_accept(lt, ld, dtok, u, 1.0, 0, k, y, None, ws)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            spd.spd_speculative_accept(lt, ld, dtok, u, 1.0, 0, k, y, None, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        abytes = n_seqs * (2 * args.gamma + 1) * V * 4
+        per_sigma[str(sigma)] = {"us": us, "GBps": abytes / (us * 1e-6) / 1e9, "mean_accepted": float(k.float().mean())}
+    res["accept_kernel"] = {"workload": f"{n_seqs} sequences x (gamma+1={args.gamma + 1}) rows x vocab {V}, logit inputs, temperature 1; "
+                                        "draft logits = target + N(0, sigma^2)",
+                            "algorithmic_bytes": n_seqs * (2 * args.gamma + 1) * V * 4, "by_sigma": per_sigma,
+                            "note": "inputs (73.7 MB) stay in the memory-side cache between repetitions"}
+    return res
 
 
 def main():
@@ -195,6 +261,8 @@ def main():
                      "bytes_per_launch": dom_bytes, "ms_per_launch": dom_ms},
         "kernels": kinds,
     }
+    if not args.no_side_configs:
+        out["other_configs"] = side_configs(args, spd, synth, torch)
     if args.calib_copy > 0:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)

@@ -195,12 +195,13 @@ int32_t spd_speculative_accept(const float *target, const float *draft, const in
 #define SPD_TRACE_KINDS 8
 int32_t spd_trace_enable(spd_model *model, int32_t enable);
 int32_t spd_trace_read(spd_model *model, int32_t n_kinds, double *h_ms_sum, int32_t *h_count);
-/* Stage timeline of the LAST whole-forward kernel launched while tracing was enabled, as seen
- * by workgroup 0: for each stage (input rows; per layer QKV, attention, O, gate|up, down; LM
- * head) the microseconds it spent working and then waiting at the device-wide barrier.
- * Blocks the host (synchronous copy).  h_us_work / h_us_wait: [max_stages]. */
-int32_t spd_trace_stages(spd_model *model, int32_t max_stages, double *h_us_work, double *h_us_wait,
-                         int32_t *h_n_stages);
+/* Stage timeline of the LAST whole-forward kernel launched while tracing was enabled.  Stage i
+ * (input rows; per layer QKV, attention, O, gate|up, down; LM head) ends at device-wide barrier
+ * i; for every barrier, in microseconds since the kernel's first workgroup started: when the
+ * first and the last workgroup arrived at it and when the first and the last workgroup left
+ * it.  Blocks the host (synchronous copy).  Each array: [max_stages]. */
+int32_t spd_trace_stages(spd_model *model, int32_t max_stages, double *h_first_arrive, double *h_last_arrive,
+                         double *h_first_leave, double *h_last_leave, int32_t *h_n_stages);
 
 #ifdef __cplusplus
 }

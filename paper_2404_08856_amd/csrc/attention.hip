@@ -1,21 +1,24 @@
-// RoPE + KV-cache append + causal attention of M <= 8 new queries per sequence over the
-// cached prefix (image rows + text + already accepted tokens), on the matrix cores.
+// RoPE + KV-cache append + causal attention of up to 5 new queries per sequence and launch over
+// the cached prefix (image rows + text + already accepted tokens), on the matrix cores.  A call
+// with 6..8 rows per sequence takes two launches: the second sees the first one's rows in the
+// cache like any other prefix position.
 //
-// One workgroup (8 waves) per (sequence, head, half of the head dimension).  The cached
+// One workgroup (12 waves) per (sequence, head, half of the head dimension).  The cached
 // keys are cut into units of 32; every wave owns a contiguous run of units and walks it
-// 3 units (96 keys) at a time.  All loads of an iteration -- the K rows and the V columns of
+// 2 units (64 keys) at a time (3 units per wave do not fit the register file next to the
+// three-term operands; 12 waves x 2 units keep the same 768 keys per round trip).  All loads of an iteration -- the K rows and the V columns of
 // the wave's keys -- are issued before anything is computed, so for contexts up to 768 keys
 // the whole kernel pays a single HBM round trip.  There is no cross-workgroup merge: the
 // two workgroups of a head both score all keys (K is read twice, V once) and each produces
 // its own half of the output dimensions.
 //
 //   scores  S[key, m] = sum_d K[key, d] q[m, d]     v_mfma_f32_16x16x32_bf16, A = 16 keys x 32 dims
-//           of the bf16 cache as stored, B = q as bf16 head (columns 0..7) + bf16 tail
-//           (columns 8..15), so S is exact up to float32 rounding of q.
+//           of the bf16 cache as stored, B = q as three bf16 terms (columns m, m + 5, m + 10 of
+//           query m), so S is exact up to float32 rounding of q.
 //   softmax per wave with running max / sum ("online"), wavefront shuffles for the
 //           reductions across the 4 lane groups.
 //   output  O[d, m] = sum_key V[key, d] p[m, key]   A = 16 dims x 32 keys of the TRANSPOSED V
-//           cache (keys contiguous), B = p as bf16 head + tail.
+//           cache (keys contiguous), B = p as three bf16 terms.
 // The rows of the two score tiles of a unit are assigned to keys so that each lane ends up
 // with the probabilities of 8 consecutive keys, which is exactly the B-operand slot of the
 // second product: no data moves between lanes.
@@ -29,12 +32,19 @@
 
 namespace spd {
 
-constexpr int kAttnWaves = 8;
-constexpr int kUnitsPerIter = 3;      // units of 32 keys per wave per iteration
+constexpr int kAttnWaves = 12;
+constexpr int kUnitsPerIter = 2;      // units of 32 keys per wave per iteration
 
 __device__ __forceinline__ f32x4_t mfma16(const uint4 &a, const uint4 &b, f32x4_t c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
                                                    __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
+// x rounded to the nearest bf16 (ties to even), as a float; x finite
+__device__ __forceinline__ float rne_bf16(float x) {
+    uint32_t b = __float_as_uint(x);
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return __uint_as_float(b & 0xffff0000u);
 }
 
 __device__ __forceinline__ uint32_t pack2(uint16_t lo, uint16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
@@ -50,8 +60,9 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attention_kernel(AttnArgs a) 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g = lane >> 4;
-    const int M = a.M, H = a.H;
-    const int P = a.lens.len[seq];                // cached positions before this call
+    const int M = a.Mq, H = a.H;                  // queries of this launch
+    const int P = a.lens.len[seq] + a.m0;         // cached positions before this launch's rows
+    const int row_base = seq * a.M + a.m0;        // first row of this launch in qkv / xout
     const int dim0 = ds * DW;
     const size_t pair = (size_t)seq * H + hh;
     const size_t HD = (size_t)H * DH;
@@ -102,7 +113,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attention_kernel(AttnArgs a) 
             float qa = 0.f, qc = 0.f;
             if (i < M) {
                 const int pos = P + i;
-                const float *row = a.qkv + (size_t)(seq * M + i) * 3 * HD + (size_t)hh * DH;
+                const float *row = a.qkv + (size_t)(row_base + i) * 3 * HD + (size_t)hh * DH;
                 const float c = a.rope[((size_t)pos * HALF + j) * 2 + 0];
                 const float s = a.rope[((size_t)pos * HALF + j) * 2 + 1];
                 const float q1 = row[j], q2 = row[j + HALF];
@@ -129,21 +140,29 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attention_kernel(AttnArgs a) 
             }
             qf[i][j] = qa;
             qf[i][j + HALF] = qc;
-            // B operand: column i holds the bf16 head of q_i, column i + 8 the bf16 tail
-            uint16_t h1, l1, h2, l2;
-            split_hi_lo(qa, h1, l1);
-            split_hi_lo(qc, h2, l2);
-            const int d1 = j, d2 = j + HALF;
-            qb[d1 >> 5][i + 16 * ((d1 & 31) >> 3)][d1 & 7] = h1;
-            qb[d1 >> 5][i + 8 + 16 * ((d1 & 31) >> 3)][d1 & 7] = l1;
-            qb[d2 >> 5][i + 16 * ((d2 & 31) >> 3)][d2 & 7] = h2;
-            qb[d2 >> 5][i + 8 + 16 * ((d2 & 31) >> 3)][d2 & 7] = l2;
+            // B operand: column i + 5 t holds bf16 term t of q_i (rows 5..7 of the loop carry zeros)
+            if (i < kGroupRows) {
+                uint16_t t1[kTerms], t2[kTerms];
+                split3(qa, t1);
+                split3(qc, t2);
+                const int d1 = j, d2 = j + HALF;
+#pragma unroll
+                for (int t = 0; t < kTerms; ++t) {
+                    qb[d1 >> 5][i + kGroupRows * t + 16 * ((d1 & 31) >> 3)][d1 & 7] = t1[t];
+                    qb[d2 >> 5][i + kGroupRows * t + 16 * ((d2 & 31) >> 3)][d2 & 7] = t2[t];
+                }
+            } else if (i == kGroupRows) {             // column 15 (unused): keep it finite
+                qb[j >> 5][15 + 16 * ((j & 31) >> 3)][j & 7] = 0;
+                qb[(j + HALF) >> 5][15 + 16 * (((j + HALF) & 31) >> 3)][(j + HALF) & 7] = 0;
+            }
         }
     }
     __syncthreads();
 
     // ---- cached keys on the matrix cores ----------------------------------------------------
-    float m_run = -INFINITY, l_run = 0.f;         // per query column r & 7 (replicated over lane groups)
+    float m_run = -INFINITY, l_run = 0.f;         // of query r % 5 (replicated over lane groups and terms)
+    const int qsrc = (lane & 48) + (r % kGroupRows);                   // lane holding term 0 of this lane's query
+    const float sel0 = r < 5 ? 1.f : 0.f, sel1 = (r >= 5 && r < 10) ? 1.f : 0.f, sel2 = (r >= 10 && r < 15) ? 1.f : 0.f;
     f32x4_t acc_o[NDT];
 #pragma unroll
     for (int i = 0; i < NDT; ++i) acc_o[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -153,77 +172,68 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attention_kernel(AttnArgs a) 
 
     for (int u0 = u_begin; u0 < u_end; u0 += UPI) {
         if (u0 != u_begin) issue_loads(u0);
-        float sv[UPI][2][4];
-        float mx = -INFINITY;
+        // one online-softmax step per unit of 32 keys: its K registers die after the scores, its V
+        // registers after the second product, so the units' temporaries never coexist
 #pragma unroll
         for (int s = 0; s < UPI; ++s) {
             const int unit = u0 + s;
+            if (unit >= u_end) break;                                  // wave-uniform
+            float sv[2][4];
+            float mx = -INFINITY;
 #pragma unroll
             for (int ab = 0; ab < 2; ++ab) {
                 f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-                if (unit < u_end) {
 #pragma unroll
-                    for (int c = 0; c < NC; ++c) acc = mfma16(kreg[s][ab][c], qreg[c], acc);
-                }
+                for (int c = 0; c < NC; ++c) acc = mfma16(kreg[s][ab][c], qreg[c], acc);
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    float x = acc[v];
-                    x += __shfl_xor(x, 8);                             // head + tail columns
+                    float x = acc[v];                                  // the three term columns of this lane's query
+                    x = __shfl(x, qsrc) + __shfl(x, qsrc + kGroupRows) + __shfl(x, qsrc + 2 * kGroupRows);
                     const int key = 32 * unit + 8 * g + 4 * ab + v;    // D row 4g + v of tile ab
-                    x = (unit < u_end && key < P) ? x : -INFINITY;
-                    sv[s][ab][v] = x;
+                    x = key < P ? x : -INFINITY;
+                    sv[ab][v] = x;
                     mx = fmaxf(mx, x);
                 }
             }
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);                          // finite: the wave has >= 1 valid key
-        const float rescale = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);
-        float lsum = 0.f;
-        uint4 pb[UPI];
-#pragma unroll
-        for (int s = 0; s < UPI; ++s) {
-            uint16_t hv[8];
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run, mx);                      // finite: a unit has >= 1 valid key
+            const float rescale = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);
+            float lsum = 0.f;
+            uint32_t hv[8];
 #pragma unroll
             for (int ab = 0; ab < 2; ++ab)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const float p = expf(sv[s][ab][v] - m_new);        // exp(-inf) = 0 for masked keys
+                    const float p = expf(sv[ab][v] - m_new);           // exp(-inf) = 0 for masked keys
                     lsum += p;
-                    uint16_t hi, lo;
-                    split_hi_lo(p, hi, lo);
-                    hv[4 * ab + v] = (r < 8) ? hi : lo;                // columns 0..7 head, 8..15 tail
+                    // this lane's column carries term r / 5 of query r % 5: p, p - t0 or p - t0 - t1
+                    const float r1 = p - rne_bf16(p);
+                    const float r2 = r1 - rne_bf16(r1);
+                    hv[4 * ab + v] = __float_as_uint(rne_bf16(sel0 * p + sel1 * r1 + sel2 * r2)) >> 16;
                 }
-            pb[s] = uint4{pack2(hv[0], hv[1]), pack2(hv[2], hv[3]), pack2(hv[4], hv[5]), pack2(hv[6], hv[7])};
-        }
-        lsum += __shfl_xor(lsum, 16);
-        lsum += __shfl_xor(lsum, 32);
-        l_run = l_run * rescale + lsum;
-        m_run = m_new;
+            const uint4 pb = uint4{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16), hv[4] | (hv[5] << 16), hv[6] | (hv[7] << 16)};
+            lsum += __shfl_xor(lsum, 16);
+            lsum += __shfl_xor(lsum, 32);
+            l_run = l_run * rescale + lsum;
+            m_run = m_new;
 #pragma unroll
-        for (int i = 0; i < NDT; ++i) {
+            for (int i = 0; i < NDT; ++i) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) acc_o[i][v] *= rescale;
-        }
-#pragma unroll
-        for (int s = 0; s < UPI; ++s) {
-            if (u0 + s < u_end) {
-#pragma unroll
-                for (int i = 0; i < NDT; ++i) acc_o[i] = mfma16(vreg[s][i], pb[s], acc_o[i]);
+                for (int v = 0; v < 4; ++v) acc_o[i][v] *= rescale;
+                acc_o[i] = mfma16(vreg[s][i], pb, acc_o[i]);
             }
         }
     }
-    // partial of this wave: O[dim 16 i + 4 g + v][column r]; head + tail columns summed
+    // partial of this wave: O[dim 16 i + 4 g + v][column r]; the three term columns summed
 #pragma unroll
     for (int i = 0; i < NDT; ++i)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            float x = acc_o[i][v];
-            x += __shfl_xor(x, 8);
-            if (r < 8) part_o[w][r][16 * i + 4 * g + v] = x;
+            const float x = sum_terms(acc_o[i][v]);
+            if (r < kGroupRows) part_o[w][r][16 * i + 4 * g + v] = x;
         }
-    if (lane < 8) { part_m[w][lane] = m_run; part_l[w][lane] = l_run; }
+    if (lane < kGroupRows) { part_m[w][lane] = m_run; part_l[w][lane] = l_run; }
 
     // ---- the M new keys (causal among the new rows), float32 from LDS -----------------------
     if (w == kAttnWaves - 1) {
@@ -272,16 +282,17 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attention_kernel(AttnArgs a) 
             den += wg * part_l[p][m];
             num += wg * part_o[p][m][dd];
         }
-        uint16_t hi, lo;
-        split_hi_lo(num / den, hi, lo);
-        const int row = seq * M + m, k = hh * DH + dim0 + dd;
-        ((uint16_t *)a.xout)[xpack_index(row, k, KS, 0)] = hi;
-        ((uint16_t *)a.xout)[xpack_index(row, k, KS, 1)] = lo;
+        uint16_t t3[kTerms];
+        split3(num / den, t3);
+        const int row = row_base + m, k = hh * DH + dim0 + dd;
+#pragma unroll
+        for (int t = 0; t < kTerms; ++t) ((uint16_t *)a.xout)[xpack_index(row, k, KS, t)] = t3[t];
     }
 }
 
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream) {
     if (a.M < 1 || a.M > 8 || (a.v_stride % 32) != 0 || a.v_stride < a.max_positions) return hipErrorInvalidValue;
+    if (a.Mq < 1 || a.Mq > kGroupRows || a.m0 < 0 || a.m0 + a.Mq > a.M) return hipErrorInvalidValue;
     if (a.dh == 128) {
         hipLaunchKernelGGL((attention_kernel<128, 2>), dim3(2, a.H, a.n_seqs), dim3(kAttnWaves * 64), 0, stream, a);
     } else if (a.dh == 64) {

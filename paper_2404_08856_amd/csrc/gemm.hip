@@ -83,7 +83,8 @@ __device__ __forceinline__ uint4 load_stream(const uint4 *p) {
 struct GemmKernelArgs {
     const uint4 *W;
     const uint4 *X;
-    int KS, n_tiles, rows;
+    int KS, n_tiles;
+    int row0, rows;           // this launch covers rows row0 .. row0 + rows - 1 (row0 a multiple of 5)
     float *Y;
     int ldy;
     const float *ssq_in;      // [ssq_in_parts][64] partial sums of squares of the input rows, or NULL
@@ -104,6 +105,7 @@ struct GemmKernelArgs {
 // cross-wave reduction or during the epilogue.
 template <int NG, int WAVES, int EPI, int U>
 __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs a) {
+    static_assert(NG * 128 <= WAVES * 64, "one epilogue thread per (group, row slot, column)");
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known uniform
     const int KS = a.KS;
@@ -115,6 +117,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs 
 
     __shared__ float red[2][WAVES][NG][16][8];
     __shared__ float inv_s[kMaxRows];
+    const int g0 = a.row0 / kGroupRows;                   // first row group of this launch (row0 % 5 == 0)
 
     uint4 av[U], bv[NG][U];
     int t = blockIdx.x;
@@ -124,12 +127,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs 
             if (u < ns) {
                 av[u] = load_stream(a.W + ((size_t)t * KS + s0 + u) * 64 + lane);
 #pragma unroll
-                for (int g = 0; g < NG; ++g) bv[g][u] = a.X[((size_t)g * KS + s0 + u) * 64 + lane];
+                for (int g = 0; g < NG; ++g) bv[g][u] = a.X[((size_t)(g0 + g) * KS + s0 + u) * 64 + lane];
             }
     }
     // 1 / rms of every input row from the producer's per-tile partial sums (fixed order)
     if (a.ssq_in) {
-        for (int r = w; r < a.rows; r += WAVES) {
+        for (int r = a.row0 + w; r < a.row0 + a.rows; r += WAVES) {
             float sum = 0.f;
             for (int p = lane; p < a.ssq_in_parts; p += 64) sum += a.ssq_in[(size_t)p * kMaxRows + r];
 #pragma unroll
@@ -147,9 +150,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs 
         // epilogue element of this thread (threads < NG * 128): fetch the old residual early
         const int e = threadIdx.x;
         const int en = e & 15, em = (e >> 4) & 7, eg = e >> 7;
-        const int erow = eg * 8 + em;
-        const bool e_active = (EPI != EPI_SWIGLU) ? (e < NG * 128 && erow < a.rows)
-                                                  : (e < NG * 128 && erow < a.rows && en < 8);
+        const int erow = a.row0 + eg * kGroupRows + em;               // absolute row of the call
+        const bool e_in = e < NG * 128 && em < kGroupRows && erow < a.row0 + a.rows;
+        const bool e_active = (EPI != EPI_SWIGLU) ? e_in : (e_in && en < 8);
         float hold = 0.f;
         if (EPI == EPI_RESIDUAL && e_active) hold = a.Y[(size_t)erow * a.ldy + (size_t)t * 16 + en];
 
@@ -173,7 +176,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs 
                 av[u] = load_stream(wsrc + woff * 64 + lane);
                 const int xs = same ? s0 + i2 : s0 + u;
 #pragma unroll
-                for (int g = 0; g < NG; ++g) bv[g][u] = a.X[((size_t)g * KS + xs) * 64 + lane];
+                for (int g = 0; g < NG; ++g) bv[g][u] = a.X[((size_t)(g0 + g) * KS + xs) * 64 + lane];
                 __builtin_amdgcn_sched_barrier(0);        // keep "consume slot, refill slot" in program order
             }
         }
@@ -186,19 +189,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs 
                     if (has_next) {
                         av[u] = load_stream(a.W + ((size_t)tn * KS + s0 + u) * 64 + lane);
 #pragma unroll
-                        for (int g = 0; g < NG; ++g) bv[g][u] = a.X[((size_t)g * KS + s0 + u) * 64 + lane];
+                        for (int g = 0; g < NG; ++g) bv[g][u] = a.X[((size_t)(g0 + g) * KS + s0 + u) * 64 + lane];
                     }
                 }
             }
         }
-        // D[n = 4 (lane / 16) + v][c = lane % 16]; columns c and c + 8 are head and tail of row c
+        // D[n = 4 (lane / 16) + v][c = lane % 16]; columns c, c + 5, c + 10 are the three terms of row c
 #pragma unroll
         for (int g = 0; g < NG; ++g)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                float x = acc[g][v];
-                float y = __shfl_xor(x, 8);
-                if ((lane & 15) < 8) red[parity][w][g][4 * (lane >> 4) + v][lane & 7] = x + y;
+                const float x = sum_terms(acc[g][v]);
+                if ((lane & 15) < kGroupRows) red[parity][w][g][4 * (lane >> 4) + v][lane & 15] = x;
             }
         __syncthreads();
 
@@ -215,10 +217,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs 
                 up *= inv_s[erow];
                 float val = gate / (1.0f + expf(-gate)) * up;
                 int f = t * 8 + en;
-                uint16_t hi, lo;
-                split_hi_lo(val, hi, lo);
-                a.Xout[xpack_index(erow, f, a.KS_out, 0)] = hi;
-                a.Xout[xpack_index(erow, f, a.KS_out, 1)] = lo;
+                uint16_t t3[kTerms];
+                split3(val, t3);
+#pragma unroll
+                for (int q = 0; q < kTerms; ++q) a.Xout[xpack_index(erow, f, a.KS_out, q)] = t3[q];
             }
         } else if (e < NG * 128) {
             float sum = 0.f;
@@ -233,11 +235,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs 
                 if (e_active) {
                     a.Y[(size_t)erow * a.ldy + col] = hnew;
                     if (a.gain_next) {
-                        uint16_t hi, lo;
-                        split_hi_lo(hnew * a.gain_next[col], hi, lo);
+                        uint16_t t3[kTerms];
+                        split3(hnew * a.gain_next[col], t3);
                         const int KSn = a.n_tiles / 2;               // N / 32
-                        a.Xnext[xpack_index(erow, col, KSn, 0)] = hi;
-                        a.Xnext[xpack_index(erow, col, KSn, 1)] = lo;
+#pragma unroll
+                        for (int q = 0; q < kTerms; ++q) a.Xnext[xpack_index(erow, col, KSn, q)] = t3[q];
                     }
                 }
                 // sum of squares of the 16 new values of this row in this tile (lanes en = 0..15)
@@ -314,9 +316,8 @@ __global__ __launch_bounds__(WAVES * 64, (NB <= 8 ? 4 : 2)) void gemm_regb_kerne
         }
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            float x = acc[v];
-            float y = __shfl_xor(x, 8);
-            if ((lane & 15) < 8) red[parity][w][4 * (lane >> 4) + v][lane & 7] = x + y;
+            const float x = sum_terms(acc[v]);
+            if ((lane & 15) < kGroupRows) red[parity][w][4 * (lane >> 4) + v][lane & 15] = x;
         }
         __syncthreads();
         if (!my_turn) continue;
@@ -333,10 +334,10 @@ __global__ __launch_bounds__(WAVES * 64, (NB <= 8 ? 4 : 2)) void gemm_regb_kerne
                 up *= inv_row;
                 float val = gate / (1.0f + expf(-gate)) * up;
                 int f = t * 8 + en;
-                uint16_t hi, lo;
-                split_hi_lo(val, hi, lo);
-                a.Xout[xpack_index(em, f, a.KS_out, 0)] = hi;
-                a.Xout[xpack_index(em, f, a.KS_out, 1)] = lo;
+                uint16_t t3[kTerms];
+                split3(val, t3);
+#pragma unroll
+                for (int q = 0; q < kTerms; ++q) a.Xout[xpack_index(em, f, a.KS_out, q)] = t3[q];
             }
         } else {
             float sum = 0.f;
@@ -351,11 +352,11 @@ __global__ __launch_bounds__(WAVES * 64, (NB <= 8 ? 4 : 2)) void gemm_regb_kerne
                 if (e_active) {
                     a.Y[(size_t)em * a.ldy + col] = hnew;
                     if (a.gain_next) {
-                        uint16_t hi, lo;
-                        split_hi_lo(hnew * a.gain_next[col], hi, lo);
+                        uint16_t t3[kTerms];
+                        split3(hnew * a.gain_next[col], t3);
                         const int KSn = a.n_tiles / 2;
-                        a.Xnext[xpack_index(em, col, KSn, 0)] = hi;
-                        a.Xnext[xpack_index(em, col, KSn, 1)] = lo;
+#pragma unroll
+                        for (int q = 0; q < kTerms; ++q) a.Xnext[xpack_index(em, col, KSn, q)] = t3[q];
                     }
                 }
                 float sq = hnew * hnew;
@@ -422,6 +423,7 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStre
     k.X = (const uint4 *)a.X;
     k.KS = (a.K + 31) / 32;
     k.n_tiles = a.N / 16;
+    k.row0 = 0;
     k.rows = a.rows;
     k.Y = a.Y;
     k.ldy = a.ldy;
@@ -434,11 +436,10 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStre
     k.ssq_out = a.ssq_out;
     k.Xout = (uint16_t *)a.Xout;
     k.KS_out = (a.K_out + 31) / 32;
-    const int groups = (a.rows + 7) / 8;
+    const int groups = (a.rows + kGroupRows - 1) / kGroupRows;
     int waves = tune.waves;
     if (waves != 4 && waves != 8 && waves != 16) waves = 8;
     if (groups > 1 && waves == 16) waves = 8;            // 16 waves need <= 128 VGPRs: only the 1-group ring fits
-    if (groups > 4) waves = 4;
     int cap = tune.grid_cap > 0 ? tune.grid_cap : (waves == 4 ? 1024 : (waves == 8 ? 512 : 256));
     const int grid = pick_grid(k.n_tiles, cap);
     if (groups == 1 && !tune.no_regb) {
@@ -461,16 +462,20 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStre
         if (waves == 8) SPD_GEMM_CASE(1, 8, 8);
         SPD_GEMM_CASE(1, 16, 8);
     }
-    if (groups == 2) {
-        if (waves == 4) SPD_GEMM_CASE(2, 4, 8);
-        SPD_GEMM_CASE(2, 8, 8);
-    }
-    if (groups <= 4) {
-        if (waves == 4) SPD_GEMM_CASE(4, 4, 4);
-        SPD_GEMM_CASE(4, 8, 4);
-    }
-    SPD_GEMM_CASE(8, 4, 4);
 #undef SPD_GEMM_CASE
+    // More than 5 rows: passes over the weights of up to 4 row groups (20 rows) each.  Every pass
+    // re-reads the matrix, so large batches pay for it; they are functional, not tuned.
+    for (int g0 = 0; g0 < groups; g0 += 4) {
+        const int ng = groups - g0 < 4 ? groups - g0 : 4;
+        k.row0 = g0 * kGroupRows;
+        k.rows = a.rows - k.row0 < ng * kGroupRows ? a.rows - k.row0 : ng * kGroupRows;
+        hipError_t e;
+        if (ng == 1) e = (waves == 4) ? launch_epi<1, 4, 8>(k, epilogue, grid, stream) : launch_epi<1, 8, 8>(k, epilogue, grid, stream);
+        else if (ng == 2) e = (waves == 4) ? launch_epi<2, 4, 8>(k, epilogue, grid, stream) : launch_epi<2, 8, 8>(k, epilogue, grid, stream);
+        else e = launch_epi<4, 8, 4>(k, epilogue, grid, stream);   // the epilogue needs 128 threads per row group
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace spd

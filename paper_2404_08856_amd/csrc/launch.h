@@ -60,6 +60,8 @@ struct AttnArgs {
     void *v_cache;           // this layer: bf16 [max_seqs, H, dh, v_stride]        (V transposed)
     void *xout;              // packed activations, K = H * dh (attention output)
     int n_seqs, M, H, dh, max_positions, v_stride;
+    int m0, Mq;              // this launch handles rows m0 .. m0 + Mq - 1 of every sequence (Mq <= 5); rows
+                             // 0 .. m0 - 1 were appended to the cache by an earlier launch
     SeqLens lens;            // KV length of every sequence before this call
 };
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream);
@@ -79,7 +81,7 @@ struct MegaArgs {
     float *h, *hg, *qkv, *att, *xf, *ssq_a, *ssq_b;    // ssq_*: [d / 16][8]
     unsigned *bar;                            // arrival counter of the device-wide barrier (only grows)
     int *abort_flag;                          // set if a barrier wait hit its spin limit
-    unsigned long long *stage_clock;          // NULL, or [2 * (barriers + 1)] wall-clock stamps of workgroup 0
+    unsigned long long *stage_clock;          // NULL, or [grid][2 * (barriers + 1)] wall-clock stamps
     // this call
     const int32_t *tokens;                    // [rows] or NULL
     const float *embeds;                      // [rows][d] or NULL
@@ -92,6 +94,7 @@ struct MegaArgs {
 hipError_t launch_megakernel(const MegaArgs &a, int grid, hipStream_t stream);
 int megakernel_max_grid(int dh);              // 0 if the kernel cannot be made resident
 constexpr int kMegaBarriersPerLayer = 5;
+constexpr int kMegaMaxGrid = 1024;        // upper bound of the whole-forward kernel's grid (one workgroup per CU)
 
 // ---- sampling ---------------------------------------------------------------------
 struct AcceptArgs {

@@ -1,5 +1,5 @@
-// One persistent kernel for a whole decoder forward over up to 8 rows (the verify step at
-// gamma + 1 <= 8, a draft step, an 8-row prefill pass).
+// One persistent kernel for a whole decoder forward over up to 5 rows = one row group (the
+// verify step at gamma + 1 <= 5, a draft step, a prefill pass).
 //
 // Why: at 5 rows every projection is a 5-15 us stream over its weights, and a layer is five
 // dependent stages (QKV, attention, O, gate|up, down).  As separate launches each stage pays
@@ -10,8 +10,8 @@
 // stage's weights while the current stage drains and the barrier is crossed.  The O
 // projection's entire weight matrix streams in while attention runs.
 //
-// Data between stages lives in small float32 row-major arrays ([8][K]); a consumer rebuilds
-// its matrix-core B operand (bf16 head | tail, see common.h) from them in registers.
+// Data between stages lives in small float32 row-major arrays ([8][K], 5 rows used); a consumer
+// rebuilds its matrix-core B operand (three bf16 terms, see common.h) from them in registers.
 // Workgroups run on different XCDs, each with its own L2, so these arrays are written with
 // device-scope (write-through) stores and read with device-scope (L2-bypassing) loads; a
 // producer waits for its stores to be acknowledged before it arrives at the barrier.
@@ -82,16 +82,23 @@ __device__ __forceinline__ void grid_barrier(unsigned *bar, unsigned target, int
 // re-arrange the head/tail halves into operand order (lane c + 16 g: column c, k = 8 g .. 8 g + 7).
 __device__ __forceinline__ uint4 to_b_operand(fx4 raw, bool row_valid, uint2 *conv, int lane) {
     const int rho = lane >> 3, kap = lane & 7;
-    union { uint2 v; uint16_t h[4]; } hi, lo;
+    union { uint2 v; uint16_t h[4]; } term[kTerms];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         float x = row_valid ? raw[e] : 0.f;
-        split_hi_lo(x, hi.h[e], lo.h[e]);
+        uint16_t t3[kTerms];
+        split3(x, t3);
+#pragma unroll
+        for (int t = 0; t < kTerms; ++t) term[t].h[e] = t3[t];
     }
     const int g = kap >> 1, half = kap & 1;
     asm volatile("" ::: "memory");                      // keep the LDS accesses below in program order
-    conv[(rho + 16 * g) * 2 + half] = hi.v;             // column rho: head
-    conv[(rho + 8 + 16 * g) * 2 + half] = lo.v;         // column rho + 8: tail
+    if (rho < kGroupRows) {                             // column rho + 5 t: bf16 term t of row rho
+#pragma unroll
+        for (int t = 0; t < kTerms; ++t) conv[(rho + kGroupRows * t + 16 * g) * 2 + half] = term[t].v;
+    } else if (rho == kGroupRows) {                     // column 15 is unused: keep it zero
+        conv[(15 + 16 * g) * 2 + half] = uint2{0u, 0u};
+    }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // LDS ops of one wave complete in order
     uint2 a0 = conv[lane * 2], a1 = conv[lane * 2 + 1];
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -237,9 +244,8 @@ __device__ __forceinline__ void gemm_stage(const GemmStage &st, uint4 (&ring)[kR
         // D[n = 4 (lane / 16) + v][c = lane % 16]; columns c and c + 8 are head and tail of row c
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            float x = acc[v];
-            float y = __shfl_xor(x, 8);
-            if ((lane & 15) < 8) red[parity][w][4 * (lane >> 4) + v][lane & 7] = x + y;
+            const float x = sum_terms(acc[v]);
+            if ((lane & 15) < kGroupRows) red[parity][w][4 * (lane >> 4) + v][lane & 15] = x;
         }
         __syncthreads();
         if (!my_turn) continue;
@@ -378,19 +384,26 @@ __device__ __forceinline__ void attention_item(const MegaAttn &a, int ds, int hh
             }
             qf[i][j] = qa;
             qf[i][j + HALF] = qc;
-            uint16_t h1, l1, h2, l2;
-            split_hi_lo(qa, h1, l1);
-            split_hi_lo(qc, h2, l2);
-            const int d1 = j, d2 = j + HALF;
-            qb[d1 >> 5][i + 16 * ((d1 & 31) >> 3)][d1 & 7] = h1;
-            qb[d1 >> 5][i + 8 + 16 * ((d1 & 31) >> 3)][d1 & 7] = l1;
-            qb[d2 >> 5][i + 16 * ((d2 & 31) >> 3)][d2 & 7] = h2;
-            qb[d2 >> 5][i + 8 + 16 * ((d2 & 31) >> 3)][d2 & 7] = l2;
+            if (i < kGroupRows) {                     // column i + 5 t: bf16 term t of q_i
+                uint16_t t1[kTerms], t2[kTerms];
+                split3(qa, t1);
+                split3(qc, t2);
+                const int d1 = j, d2 = j + HALF;
+#pragma unroll
+                for (int t = 0; t < kTerms; ++t) {
+                    qb[d1 >> 5][i + kGroupRows * t + 16 * ((d1 & 31) >> 3)][d1 & 7] = t1[t];
+                    qb[d2 >> 5][i + kGroupRows * t + 16 * ((d2 & 31) >> 3)][d2 & 7] = t2[t];
+                }
+            } else if (i == kGroupRows) {             // column 15 (unused): keep it finite
+                qb[j >> 5][15 + 16 * ((j & 31) >> 3)][j & 7] = 0;
+                qb[(j + HALF) >> 5][15 + 16 * (((j + HALF) & 31) >> 3)][(j + HALF) & 7] = 0;
+            }
         }
     }
     __syncthreads();
 
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;         // of query r % 5
+    const int qsrc = (lane & 48) + (r % kGroupRows);
     fx4 acc_o[NDT];
 #pragma unroll
     for (int i = 0; i < NDT; ++i) acc_o[i] = fx4{0.f, 0.f, 0.f, 0.f};
@@ -415,7 +428,7 @@ __device__ __forceinline__ void attention_item(const MegaAttn &a, int ds, int hh
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     float x = acc[v];
-                    x += __shfl_xor(x, 8);
+                    x = __shfl(x, qsrc) + __shfl(x, qsrc + kGroupRows) + __shfl(x, qsrc + 2 * kGroupRows);
                     const int key = 32 * unit + 8 * g + 4 * ab + v;
                     x = (unit < u_end && key < P) ? x : -INFINITY;
                     sv[s][ab][v] = x;
@@ -438,9 +451,9 @@ __device__ __forceinline__ void attention_item(const MegaAttn &a, int ds, int hh
                 for (int v = 0; v < 4; ++v) {
                     const float p = expf(sv[s][ab][v] - m_new);
                     lsum += p;
-                    uint16_t hi, lo;
-                    split_hi_lo(p, hi, lo);
-                    hv[4 * ab + v] = (r < 8) ? hi : lo;
+                    uint16_t t3[kTerms];
+                    split3(p, t3);
+                    hv[4 * ab + v] = r < 5 ? t3[0] : (r < 10 ? t3[1] : (r < 15 ? t3[2] : (uint16_t)0));
                 }
             pb[s] = uint4{pk2(hv[0], hv[1]), pk2(hv[2], hv[3]), pk2(hv[4], hv[5]), pk2(hv[6], hv[7])};
         }
@@ -463,11 +476,10 @@ __device__ __forceinline__ void attention_item(const MegaAttn &a, int ds, int hh
     for (int i = 0; i < NDT; ++i)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            float x = acc_o[i][v];
-            x += __shfl_xor(x, 8);
-            if (r < 8) part_o[w][r][16 * i + 4 * g + v] = x;
+            const float x = sum_terms(acc_o[i][v]);
+            if (r < kGroupRows) part_o[w][r][16 * i + 4 * g + v] = x;
         }
-    if (lane < 8) { part_m[w][lane] = m_run; part_l[w][lane] = l_run; }
+    if (lane < kGroupRows) { part_m[w][lane] = m_run; part_l[w][lane] = l_run; }
 
     if (w == kMW - 1) {                                 // the M new keys, float32 from LDS
         const int m = lane >> 3, j = lane & 7;
@@ -542,10 +554,11 @@ __global__ __launch_bounds__(kMW * 64) void decoder_megakernel(MegaArgs a) {
     if (b < T_qkv) prime_ring(ring, Wm(a.off_wqkv0, 0), KS_d, b, w, lane);
 
     unsigned bar_no = 0;
-    // optional tracing: workgroup 0 records, per barrier, when it arrived and when it left
-    // (100 MHz wall clock), i.e. its own work time and its wait time for every stage
+    // optional tracing: every workgroup records, per barrier, when it arrived and when it left
+    // (100 MHz wall clock)
+    const unsigned n_stamps = 2 * (2 + kMegaBarriersPerLayer * a.n_layers);
     auto stamp = [&](int slot) {
-        if (a.stage_clock && b == 0 && threadIdx.x == 0) a.stage_clock[2 * bar_no + slot] = wall_clock64();
+        if (a.stage_clock && threadIdx.x == 0) a.stage_clock[(size_t)b * n_stamps + 2 * bar_no + slot] = wall_clock64();
     };
     auto barrier = [&]() {
         stamp(0);
@@ -656,7 +669,7 @@ int megakernel_max_grid(int dh) {
         ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decoder_megakernel<128>, kMW * 64, 0)
         : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decoder_megakernel<64>, kMW * 64, 0);
     if (e != hipSuccess || per_cu < 1) return 0;
-    return cus;                                         // one workgroup per CU
+    return cus < kMegaMaxGrid ? cus : kMegaMaxGrid;     // one workgroup per CU
 }
 
 }  // namespace spd

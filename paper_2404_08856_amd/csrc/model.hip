@@ -109,7 +109,7 @@ void make_layout(const spd_model_config &c, Layout &L) {
     L.m_ssq_a = take((size_t)(d / 16) * 8 * 4);
     L.m_ssq_b = take((size_t)(d / 16) * 8 * 4);
     L.m_sync = take(256);
-    L.m_clock = take((size_t)(2 * (2 + kMegaBarriersPerLayer * c.n_layers)) * 8);
+    L.m_clock = take((size_t)kMegaMaxGrid * (2 * (2 + kMegaBarriersPerLayer * c.n_layers)) * 8);
     L.ws_total = off;
 }
 
@@ -345,7 +345,7 @@ int32_t forward(spd_model *m, const int32_t *tokens, const float *embeds, int se
         if (len + M > max_total) max_total = len + M;
     }
     const int d = c.d_model, HD = c.n_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
-    if (rows <= 8 && m->mega_grid > 0) {
+    if (rows <= kGroupRows && m->mega_grid > 0) {
         MegaArgs ma{};
         ma.packed = m->packed;
         ma.off_embed = L.embed; ma.off_lm_head = L.lm_head; ma.off_final_norm = L.final_norm;
@@ -399,7 +399,10 @@ int32_t forward(spd_model *m, const int32_t *tokens, const float *embeds, int se
         char *kv_l = m->kv + (size_t)l * L.kv_layer_stride;
         at.k_cache = kv_l + (size_t)seq0 * c.n_heads * c.max_positions * c.head_dim * 2;
         at.v_cache = kv_l + align_up(L.kv_k_bytes, 256) + (size_t)seq0 * c.n_heads * c.head_dim * L.v_stride * 2;
-        PROF_TRY(PK_ATTENTION, launch_attention(at, st));
+        for (int m0 = 0; m0 < M; m0 += kGroupRows) {         // at most 5 queries per sequence and launch
+            at.m0 = m0; at.Mq = std::min(kGroupRows, M - m0);
+            PROF_TRY(PK_ATTENTION, launch_attention(at, st));
+        }
         g = GemmArgs{};
         g.W = m->packed + L.wo[l]; g.X = xo; g.N = d; g.K = HD; g.rows = rows; g.Y = h; g.ldy = d;
         g.gain_next = gain_of(L.mlp_norm[l]); g.Xnext = xn; g.ssq_out = ssq_a;
@@ -431,8 +434,8 @@ int32_t prefill_common(spd_model *m, int32_t seq, const float *embeds, const int
     if (m->lens[seq] + n_rows > m->cfg.max_positions)
         return fail(SPD_ERR_CAPACITY, "KV cache overflow in prefill: %d + %d > %d", m->lens[seq], n_rows, m->cfg.max_positions);
     float *scratch = (float *)(m->ws + m->L.logits);
-    for (int r0 = 0; r0 < n_rows; r0 += SPD_MAX_M) {
-        int M = n_rows - r0 < SPD_MAX_M ? n_rows - r0 : SPD_MAX_M;
+    for (int r0 = 0; r0 < n_rows; r0 += kGroupRows) {        // one row group per pass: the single-group kernels
+        int M = n_rows - r0 < kGroupRows ? n_rows - r0 : kGroupRows;
         bool last = r0 + M >= n_rows;
         int32_t rc = forward(m, tokens ? tokens + r0 : nullptr, embeds ? embeds + (size_t)r0 * m->cfg.d_model : nullptr,
                              seq, 1, M, (last && last_logits) ? scratch : nullptr, st);
@@ -469,17 +472,27 @@ int32_t spd_trace_read(spd_model *m, int32_t n_kinds, double *ms_sum, int32_t *c
     return SPD_OK;
 }
 
-int32_t spd_trace_stages(spd_model *m, int32_t max_stages, double *us_work, double *us_wait, int32_t *n_stages) {
-    if (!m || !us_work || !us_wait || !n_stages || max_stages < 1) return fail(SPD_ERR_INVALID_ARG, "bad argument to spd_trace_stages");
-    const int n = 1 + kMegaBarriersPerLayer * m->cfg.n_layers + 1;          // stages separated by the barriers
-    std::vector<unsigned long long> clk((size_t)2 * (n + 1));
+int32_t spd_trace_stages(spd_model *m, int32_t max_stages, double *first_arrive, double *last_arrive,
+                         double *first_leave, double *last_leave, int32_t *n_stages) {
+    if (!m || !first_arrive || !last_arrive || !first_leave || !last_leave || !n_stages || max_stages < 1)
+        return fail(SPD_ERR_INVALID_ARG, "bad argument to spd_trace_stages");
+    if (m->mega_grid < 1) return fail(SPD_ERR_INVALID_ARG, "the whole-forward kernel is not enabled for this model");
+    const int n_bar = 1 + kMegaBarriersPerLayer * m->cfg.n_layers;            // barriers of one forward
+    const size_t n_stamps = (size_t)2 * (n_bar + 1), G = (size_t)m->mega_grid;
+    std::vector<unsigned long long> clk(G * n_stamps);
     HIP_TRY(hipMemcpy(clk.data(), m->ws + m->L.m_clock, clk.size() * 8, hipMemcpyDeviceToHost));   // blocks
-    *n_stages = n < max_stages ? n : max_stages;
+    // per workgroup: [1] = start, [2 i] = arrival at barrier i, [2 i + 1] = departure from it (i >= 1)
+    unsigned long long t0 = ~0ull;
+    for (size_t g = 0; g < G; ++g) t0 = std::min(t0, clk[g * n_stamps + 1]);
+    *n_stages = n_bar < max_stages ? n_bar : max_stages;
     for (int i = 0; i < *n_stages; ++i) {
-        // stamps: [2 i + 1] = stage i starts (left barrier i), [2 i] = its work is done (arrives at
-        // barrier i + 1), [2 (i + 1) + 1] = left barrier i + 1
-        us_work[i] = (double)(clk[2 * i] - clk[2 * i + 1]) * 0.01;
-        us_wait[i] = (i + 1 < n) ? (double)(clk[2 * (i + 1) + 1] - clk[2 * i]) * 0.01 : 0.0;
+        unsigned long long a0 = ~0ull, a1 = 0, d0 = ~0ull, d1 = 0;
+        for (size_t g = 0; g < G; ++g) {
+            const unsigned long long arr = clk[g * n_stamps + 2 * i], dep = clk[g * n_stamps + 2 * (i + 1) + 1];
+            a0 = std::min(a0, arr); a1 = std::max(a1, arr); d0 = std::min(d0, dep); d1 = std::max(d1, dep);
+        }
+        first_arrive[i] = (double)(a0 - t0) * 0.01; last_arrive[i] = (double)(a1 - t0) * 0.01;
+        first_leave[i] = (double)(d0 - t0) * 0.01; last_leave[i] = (double)(d1 - t0) * 0.01;
     }
     return SPD_OK;
 }

@@ -4,8 +4,8 @@
 
 namespace spd {
 
-// One workgroup per input row.  Writes the float32 residual row h, the packed bf16
-// head/tail operand of (h * gain) for the first QKV projection, and sum(h^2) of the row
+// One workgroup per input row.  Writes the float32 residual row h, the packed three-term bf16
+// operand of (h * gain) for the first QKV projection, and sum(h^2) of the row
 // (the RMSNorm scale itself is applied inside that projection).
 __global__ __launch_bounds__(256) void input_rows_kernel(const uint16_t *__restrict__ E,
                                                          const int32_t *__restrict__ tokens,
@@ -34,12 +34,17 @@ __global__ __launch_bounds__(256) void input_rows_kernel(const uint16_t *__restr
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
         float4 g = *reinterpret_cast<const float4 *>(gain + k);
         float y[4] = {v.x * g.x, v.y * g.y, v.z * g.z, v.w * g.w};
-        union { uint2 v; uint16_t h[4]; } hi, lo;
+        union { uint2 v; uint16_t h[4]; } term[kTerms];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) split_hi_lo(y[e], hi.h[e], lo.h[e]);
+        for (int e = 0; e < 4; ++e) {
+            uint16_t t3[kTerms];
+            split3(y[e], t3);
+#pragma unroll
+            for (int t = 0; t < kTerms; ++t) term[t].h[e] = t3[t];
+        }
         // 4 consecutive k stay inside one 8-element lane slot
-        *reinterpret_cast<uint2 *>(xpack + xpack_index(row, k, KS, 0)) = hi.v;
-        *reinterpret_cast<uint2 *>(xpack + xpack_index(row, k, KS, 1)) = lo.v;
+#pragma unroll
+        for (int t = 0; t < kTerms; ++t) *reinterpret_cast<uint2 *>(xpack + xpack_index(row, k, KS, t)) = term[t].v;
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);

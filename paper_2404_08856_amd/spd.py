@@ -70,7 +70,7 @@ _lib.spd_accept_workspace_bytes.argtypes = [_i32, _i32, _i32, _szp]
 _lib.spd_speculative_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _u32, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.spd_trace_enable.argtypes = [_vp, _i32]
 _lib.spd_trace_read.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i32)]
-_lib.spd_trace_stages.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i32)]
+_lib.spd_trace_stages.argtypes = [_vp, _i32] + [ctypes.POINTER(ctypes.c_double)] * 4 + [ctypes.POINTER(_i32)]
 for _name in EXPORTS:
     if _name != "spd_last_error":
         getattr(_lib, _name).restype = _i32
@@ -185,12 +185,12 @@ class Model:
         _check(_lib.spd_trace_enable(self.handle, int(bool(enable))))
 
     def spd_trace_stages(self, max_stages=4096):
-        """[(us working, us waiting at the barrier)] per stage of the last traced whole-forward kernel."""
-        work = (ctypes.c_double * max_stages)()
-        wait = (ctypes.c_double * max_stages)()
+        """[(first arrival, last arrival, first departure, last departure)] in us per device-wide barrier
+        of the last traced whole-forward kernel."""
+        arr = [(ctypes.c_double * max_stages)() for _ in range(4)]
         n = ctypes.c_int32()
-        _check(_lib.spd_trace_stages(self.handle, max_stages, work, wait, ctypes.byref(n)))
-        return [(work[i], wait[i]) for i in range(n.value)]
+        _check(_lib.spd_trace_stages(self.handle, max_stages, *arr, ctypes.byref(n)))
+        return [tuple(a[i] for a in arr) for i in range(n.value)]
 
     def spd_trace_read(self):
         """{kind: (milliseconds summed over launches, launches)} since the last read; waits for the events."""

@@ -196,3 +196,102 @@ def test_whole_forward_persistent_kernel_opt_in(case, monkeypatch):
         run_case(synth.SHAPES["tiny_draft"], 0, 65, 1, seed=32, extra_steps=2)
     else:
         run_case(synth.llama7b_layers(2), 576, 64, 5, seed=33)
+
+
+@pytest.mark.timeout(900)
+def test_llama7b_full_depth_against_oracle_short_context():
+    """All 32 layers of the 7B shape (every weight byte the benchmark streams) against the
+    oracle.  The oracle's cost grows with the prefix, so the prefix is 56 image rows + 8
+    text tokens here; the full 640-position prefix is covered at 2 layers above and by the
+    full-size consistency test below."""
+    shape = synth.SHAPES["llama7b"]
+    m_img, n_text, M, seed = 56, 8, 5, 41
+    print("case full-depth 7B, prefix 64, M=5", flush=True)
+    spd = spd_mod()
+    w = synth.make_weights(shape, seed, device="cuda")
+    model = spd.Model(spd.make_config(shape, 1, 80), w)
+    wn = synth.weights_to_numpy(w)
+    del w
+    torch.cuda.empty_cache()
+    cfg = oracle_cfg(shape)
+    toks = synth.text_tokens(n_text, shape.vocab, seed)
+    x = np.concatenate([synth.image_rows(m_img, shape.d_model, seed).astype(np.float64), dec.embed_tokens(wn, toks)])
+    cache = dec.KVCache(cfg, 80)
+    ref_last = dec.forward_rows(cfg, wn, cache, x)[-1]
+    print("oracle prefill done", flush=True)
+    last = torch.empty(shape.vocab, dtype=torch.float32, device="cuda")
+    model.spd_prefill(0, torch.from_numpy(x.astype(np.float32)).cuda(), last)
+    check_logits(last.cpu().numpy(), ref_last, "prefill last row")
+    vt = synth.text_tokens(M, shape.vocab, seed + 1)
+    ref = dec.forward_tokens(cfg, wn, cache, vt)
+    print("oracle verify done", flush=True)
+    out = torch.empty((1, M, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_verify_forward(torch.from_numpy(vt).cuda()[None].contiguous(), out)
+    mx, mean = check_logits(out.cpu().numpy()[0], ref, "verify")
+    print("full-depth 7B verify err", mx, mean)
+    model.close()
+
+
+def test_llama7b_full_size_benchmark_configuration_is_self_consistent():
+    """The benchmark's exact configuration (32 layers, prefix 576 image rows + 64 text tokens,
+    gamma + 1 = 5), where the oracle is out of reach: the invariants it is pinned by must hold
+    on the device -- the 5-row cached forward equals 5 single-row forwards and equals the
+    prefill path over the same tokens (cached multi-token forward = recompute)."""
+    shape = synth.SHAPES["llama7b"]
+    spd = spd_mod()
+    print("case full-size 7B benchmark configuration", flush=True)
+    model = spd.Model(spd.make_config(shape, 1, 656), synth.make_weights(shape, 0, device="cuda"))
+    torch.cuda.empty_cache()
+    model.spd_prefill(0, torch.from_numpy(synth.image_rows(576, shape.d_model, 0)).cuda())
+    model.spd_prefill_tokens(0, torch.from_numpy(synth.text_tokens(64, shape.vocab, 0)).cuda())
+    vt = torch.from_numpy(synth.text_tokens(5, shape.vocab, 1)).cuda()
+    out5 = torch.empty((1, 5, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_verify_forward(vt[None].contiguous(), out5)
+    assert model.spd_kv_get_len(1) == [645]
+    assert torch.isfinite(out5).all()
+    model.spd_kv_set_len([640])
+    out1 = torch.empty((1, 1, shape.vocab), dtype=torch.float32, device="cuda")
+    singles = []
+    for i in range(5):
+        model.spd_verify_forward(vt[i:i + 1][None].contiguous(), out1)
+        singles.append(out1[0, 0].clone())
+    singles = torch.stack(singles)
+    err = (singles - out5[0]).abs()
+    print("5-row vs single-row: max", float(err.max()), "mean", float(err.mean()))
+    assert float(err.max()) < 3e-3 and float(err.mean()) < 3e-4
+    model.spd_kv_set_len([640])
+    last = torch.empty(shape.vocab, dtype=torch.float32, device="cuda")
+    model.spd_prefill_tokens(0, vt, last)
+    err = (last - out5[0, 4]).abs()
+    print("prefill path vs verify: max", float(err.max()))
+    assert float(err.max()) < 3e-3
+    # logits of different rows differ (a row-mixing bug would survive the checks above only if rows were equal)
+    assert float((out5[0, 0] - out5[0, 4]).abs().max()) > 0.1
+    model.close()
+
+
+@pytest.mark.parametrize("n_seqs,M", [(8, 8), (8, 6), (7, 3), (2, 4), (13, 1)])
+def test_batched_verify_many_row_groups(n_seqs, M):
+    """Batches whose rows span several row groups and several passes over the weights
+    (up to 8 sequences x 8 rows = 64 rows), ragged prefix lengths, M above 5 (two
+    attention launches per layer)."""
+    print(f"case batched n_seqs={n_seqs} M={M}", flush=True)
+    shape = synth.SHAPES["tiny_target"]
+    model, wn = build_pair(shape, 17, n_seqs, 64)
+    cfg = oracle_cfg(shape)
+    caches = []
+    for s in range(n_seqs):
+        n = 3 + (7 * s) % 29
+        toks = synth.text_tokens(n, shape.vocab, 100 + s)
+        c = dec.KVCache(cfg, 64)
+        dec.forward_tokens(cfg, wn, c, toks)
+        caches.append(c)
+        model.spd_prefill_tokens(s, torch.from_numpy(toks).cuda())
+    vt = np.stack([synth.text_tokens(M, shape.vocab, 200 + s) for s in range(n_seqs)])
+    out = torch.empty((n_seqs, M, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_verify_forward(torch.from_numpy(vt).cuda(), out)
+    got = out.cpu().numpy()
+    for s in range(n_seqs):
+        check_logits(got[s], dec.forward_tokens(cfg, wn, caches[s], vt[s]), f"seq {s}")
+    assert model.spd_kv_get_len(n_seqs) == [c.length for c in caches]
+    model.close()
