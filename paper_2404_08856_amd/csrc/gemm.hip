@@ -87,12 +87,12 @@ struct GemmKernelArgs {
     int row0, rows;           // this launch covers rows row0 .. row0 + rows - 1 (row0 a multiple of 5)
     float *Y;
     int ldy;
-    const float *ssq_in;      // [ssq_in_parts][64] partial sums of squares of the input rows, or NULL
+    const float *ssq_in;      // [64][K / 16]: ssq_in_parts partial sums of squares per input row, or NULL
     int ssq_in_parts;
     float inv_d, eps;         // RMSNorm: 1 / sqrt(sum * inv_d + eps)
     const float *gain_next;   // RESIDUAL: gain of the norm that follows, or NULL
     uint16_t *Xnext;          // RESIDUAL: packed (h * gain_next), K = N
-    float *ssq_out;           // RESIDUAL: [n_tiles][64] partial sums of squares of the new h
+    float *ssq_out;           // RESIDUAL: [64][n_tiles] partial sums of squares of the new h, one per tile
     uint16_t *Xout;           // SWIGLU: packed activations, K = N / 2
     int KS_out;
 };
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs 
     if (a.ssq_in) {
         for (int r = a.row0 + w; r < a.row0 + a.rows; r += WAVES) {
             float sum = 0.f;
-            for (int p = lane; p < a.ssq_in_parts; p += 64) sum += a.ssq_in[(size_t)p * kMaxRows + r];
+            for (int p = lane; p < a.ssq_in_parts; p += 64) sum += a.ssq_in[(size_t)r * (KS * 2) + p];
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
             if (lane == 0) inv_s[r] = 1.0f / sqrtf(sum * a.inv_d + a.eps);
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs 
                 float sq = hnew * hnew;
 #pragma unroll
                 for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
-                if (a.ssq_out && en == 0 && e_active) a.ssq_out[(size_t)t * kMaxRows + erow] = sq;
+                if (a.ssq_out && en == 0 && e_active) a.ssq_out[(size_t)erow * a.n_tiles + t] = sq;
             }
         }
         // no second barrier: the next tile writes the other half of `red`
@@ -288,9 +288,20 @@ __global__ __launch_bounds__(WAVES * 64, (NB <= 8 ? 4 : 2)) void gemm_regb_kerne
     const bool row_ok = em < a.rows;
     float inv_row = 1.0f;
     if (a.ssq_in) {                                       // 1 / rms of row em from the per-tile partial sums
+        // the row's partials are contiguous: 16 lanes read them as float4, all loads in flight at once
         float sum = 0.f;
-        if (row_ok)
-            for (int p = en; p < a.ssq_in_parts; p += 16) sum += a.ssq_in[(size_t)p * kMaxRows + em];
+        if (row_ok) {
+            const float *part = a.ssq_in + (size_t)em * (KS * 2);
+            if ((a.ssq_in_parts & 3) == 0) {
+#pragma unroll 4
+                for (int p = en; p < (a.ssq_in_parts >> 2); p += 16) {
+                    const float4 q = reinterpret_cast<const float4 *>(part)[p];
+                    sum += (q.x + q.y) + (q.z + q.w);
+                }
+            } else {
+                for (int p = en; p < a.ssq_in_parts; p += 16) sum += part[p];
+            }
+        }
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
         inv_row = 1.0f / sqrtf(sum * a.inv_d + a.eps);
@@ -362,7 +373,7 @@ __global__ __launch_bounds__(WAVES * 64, (NB <= 8 ? 4 : 2)) void gemm_regb_kerne
                 float sq = hnew * hnew;
 #pragma unroll
                 for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
-                if (a.ssq_out && en == 0 && e_active) a.ssq_out[(size_t)t * kMaxRows + em] = sq;
+                if (a.ssq_out && en == 0 && e_active) a.ssq_out[(size_t)em * a.n_tiles + t] = sq;
             }
         }
     }

@@ -29,15 +29,15 @@ struct GemmArgs {
     float *Y;             // STORE: Y[row, n] = s * acc ; RESIDUAL: Y[row, n] += acc   (ld = ldy)
     int ldy;
     // RMSNorm folded into the GEMM: X holds (h * gain) un-normalised; the row scale
-    // s = 1 / sqrt(sum_sq / K + eps) is applied to the accumulator.  ssq_in[parts][64] holds
-    // partial sums of squares per row (NULL: s = 1).
+    // s = 1 / sqrt(sum_sq / K + eps) is applied to the accumulator.  ssq_in[64][K / 16] holds
+    // ssq_in_parts partial sums of squares per row (NULL: s = 1).
     const float *ssq_in;
     int ssq_in_parts;
     float eps;
     // RESIDUAL only: also emit what the next norm + GEMM needs from the new h (N % 32 == 0):
     const float *gain_next;   // gain of the following RMSNorm, or NULL
     void *Xnext;              // packed (h_new * gain_next), K = N
-    float *ssq_out;           // [N / 16][64] per-tile sums of squares of h_new
+    float *ssq_out;           // [64][N / 16] per-tile sums of squares of h_new
     void *Xout;           // SWIGLU: packed activations with K_out = N / 2 columns
     int K_out;
 };
@@ -46,7 +46,7 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStre
 // ---- row-wise kernels -------------------------------------------------------------
 // Input rows of a forward: h[row, :] = float(E[tokens[row], :]) (token ids clamped into
 // [0, vocab)) or h[row, :] = embeds[row, :]; also writes the packed (h * gain) operand of
-// the first QKV projection and the sum of squares of every row (ssq[row], one part).
+// the first QKV projection and the sum of squares of every row (ssq[row * (d / 16)], one part).
 hipError_t launch_input_rows(const void *embed_bf16, const int32_t *tokens, const float *embeds, int rows,
                              int d, int vocab, const float *gain, float *h, void *xpack, float *ssq,
                              hipStream_t stream);
@@ -66,7 +66,7 @@ struct AttnArgs {
 };
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream);
 
-// ---- whole forward in one persistent kernel (rows <= 8) -------------------------------------
+// ---- whole forward in one persistent kernel (rows <= 5) -------------------------------------
 struct MegaArgs {
     // model
     const char *packed;                       // packed weights (spd_model_create layout)

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void input_rows_kernel(const uint16_t *__restr
     __shared__ float part[4];
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
     __syncthreads();
-    if (threadIdx.x == 0) ssq[row] = (part[0] + part[1]) + (part[2] + part[3]);
+    if (threadIdx.x == 0) ssq[(size_t)row * (d / 16)] = (part[0] + part[1]) + (part[2] + part[3]);   // part 0 of [rows][d / 16]
 }
 
 hipError_t launch_input_rows(const void *embed_bf16, const int32_t *tokens, const float *embeds, int rows,

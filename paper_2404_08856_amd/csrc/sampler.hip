@@ -122,6 +122,138 @@ __device__ void row_stats(const float *__restrict__ row, int V, float inv_temp, 
     __syncthreads();
 }
 
+// ---------------------------------------------------------------------------------
+// Register-staged fast path: rows of up to 32768 entries (a multiple of 4, 16-byte aligned)
+// are read exactly once, with coalesced 16-byte loads that are all in flight together:
+// thread t holds float4 number i * 1024 + t of the row, i < kRowVec.  The generic code above
+// (any vocabulary size) walks the row with dependent loads and is several times slower.
+// ---------------------------------------------------------------------------------
+constexpr int kRowVec = 8;
+
+__device__ __forceinline__ bool row_fits_registers(const float *row, int V) {
+    return (V & 3) == 0 && V <= kRowVec * kSampThreads * 4 && (reinterpret_cast<uintptr_t>(row) & 15) == 0;
+}
+
+// entries beyond the row read as `fill`
+__device__ __forceinline__ void load_row(const float *__restrict__ row, int V, float fill, float4 (&v)[kRowVec]) {
+    const int n4 = V >> 2;
+#pragma unroll
+    for (int i = 0; i < kRowVec; ++i) {
+        const int q = i * kSampThreads + (int)threadIdx.x;
+        v[i] = q < n4 ? reinterpret_cast<const float4 *>(row)[q] : float4{fill, fill, fill, fill};
+    }
+}
+
+// softmax statistics from a row held in registers (same definition as row_stats)
+__device__ void row_stats_regs(const float4 (&v)[kRowVec], int V, float inv_temp, RowStats *out_shared) {
+    __shared__ float s_mx[kSampThreads / 64];
+    __shared__ int s_arg[kSampThreads / 64];
+    __shared__ float s_sum[kSampThreads / 64];
+    float mx = -INFINITY;
+    int arg = 0x7fffffff;
+#pragma unroll
+    for (int i = 0; i < kRowVec; ++i) {                       // ascending x within the thread
+        const int x0 = 4 * (i * kSampThreads + (int)threadIdx.x);
+        const float e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (e[j] > mx) { mx = e[j]; arg = x0 + j; }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        float om = __shfl_xor(mx, off);
+        int oa = __shfl_xor(arg, off);
+        if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
+    }
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = kSampThreads >> 6;
+    if (lane == 0) { s_mx[w] = mx; s_arg[w] = arg; }
+    __syncthreads();
+    mx = s_mx[0]; arg = s_arg[0];
+    for (int i = 1; i < nw; ++i)
+        if (s_mx[i] > mx || (s_mx[i] == mx && s_arg[i] < arg)) { mx = s_mx[i]; arg = s_arg[i]; }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < kRowVec; ++i) {                       // padding is -inf: exp gives 0
+        sum += expf((v[i].x - mx) * inv_temp);
+        sum += expf((v[i].y - mx) * inv_temp);
+        sum += expf((v[i].z - mx) * inv_temp);
+        sum += expf((v[i].w - mx) * inv_temp);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    if (lane == 0) s_sum[w] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+        for (int i = 0; i < nw; ++i) t += s_sum[i];
+        out_shared->mx = mx; out_shared->sum = t; out_shared->argmax = arg; out_shared->pad = 0;
+    }
+    __syncthreads();
+}
+
+// Inverse-CDF draw (same definition as sample_inverse_cdf) from weights given per register
+// slot: wf(i, j, x) = fixed-point weight of entry x = 4 (i * 1024 + t) + j.  The running sum
+// over x is: all of slice i' < i, then the threads before t in slice i, then entries before j.
+template <class WF>
+__device__ int sample_inverse_cdf_regs(WF wf, int V, float u, unsigned long long *tmp, int *result) {
+    // tmp: kRowVec * 17 u64 of shared memory
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    auto part_of = [&](int i) {                               // weights are recomputed rather than kept: registers
+        const int x0 = 4 * (i * kSampThreads + (int)threadIdx.x);
+        unsigned long long p = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) p += (x0 + j < V) ? wf(i, j, x0 + j) : 0ull;
+        return p;
+    };
+    unsigned long long incl[kRowVec];
+#pragma unroll
+    for (int i = 0; i < kRowVec; ++i) incl[i] = part_of(i);
+#pragma unroll
+    for (int i = 0; i < kRowVec; ++i) {
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            unsigned long long t = shfl_up_u64(incl[i], off);
+            if (lane >= off) incl[i] += t;
+        }
+    }
+    __syncthreads();                                          // tmp may still be in use by a previous call
+    if (lane == 63) {
+#pragma unroll
+        for (int i = 0; i < kRowVec; ++i) tmp[i * 17 + w] = incl[i];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {                                   // slices in order, waves in order
+        unsigned long long run = 0;
+        for (int i = 0; i < kRowVec; ++i)
+            for (int k = 0; k < kSampThreads / 64; ++k) { unsigned long long t = tmp[i * 17 + k]; tmp[i * 17 + k] = run; run += t; }
+        tmp[16] = run;                                        // slot 16 of slice 0 is free
+        *result = -1;
+    }
+    __syncthreads();
+    const unsigned long long S = tmp[16];
+    if (S != 0) {
+        const unsigned long long thr = threshold_of(u, S);
+#pragma unroll
+        for (int i = 0; i < kRowVec; ++i) {
+            const unsigned long long part = part_of(i);
+            const unsigned long long excl = tmp[i * 17 + w] + incl[i] - part;
+            if (excl <= thr && thr < excl + part) {           // exactly one (thread, slice)
+                const int x0 = 4 * (i * kSampThreads + (int)threadIdx.x);
+                unsigned long long run = excl;
+                int found = -1;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (x0 + j < V) run += wf(i, j, x0 + j);
+                    if (found < 0 && run > thr) found = x0 + j;
+                }
+                *result = found;
+            }
+        }
+    }
+    __syncthreads();
+    return *result;
+}
+
 __global__ __launch_bounds__(kSampThreads) void accept_stats_kernel(AcceptArgs a) {
     // one workgroup per logits row: target rows first, then draft rows
     const int n_t = a.n_seqs * (a.gamma + 1);
@@ -132,7 +264,13 @@ __global__ __launch_bounds__(kSampThreads) void accept_stats_kernel(AcceptArgs a
     const float *row = is_t ? a.target + (size_t)r * a.vocab : a.draft + (size_t)(r - n_t) * a.vocab;
     const float inv_temp = a.temperature > 0.f ? 1.0f / a.temperature : 1.0f;
     __shared__ RowStats st;
-    row_stats(row, a.vocab, inv_temp, &st);
+    if (row_fits_registers(row, a.vocab)) {
+        float4 v[kRowVec];
+        load_row(row, a.vocab, -INFINITY, v);
+        row_stats_regs(v, a.vocab, inv_temp, &st);
+    } else {
+        row_stats(row, a.vocab, inv_temp, &st);
+    }
     if (threadIdx.x == 0) reinterpret_cast<RowStats *>(a.stats)[r] = st;
 }
 
@@ -142,10 +280,12 @@ struct RowProb {
     RowStats st;
     float inv_temp;
     int mode;           // 0 probabilities, 1 softmax of logits, 2 greedy one-hot
-    __device__ __forceinline__ float operator()(int x) const {
-        if (mode == 0) return row[x];
+    __device__ __forceinline__ float operator()(int x) const { return of(row[x], x); }
+    // probability of token x whose row entry is `value`
+    __device__ __forceinline__ float of(float value, int x) const {
+        if (mode == 0) return value;
         if (mode == 2) return x == st.argmax ? 1.0f : 0.0f;
-        return expf((row[x] - st.mx) * inv_temp) / st.sum;
+        return expf((value - st.mx) * inv_temp) / st.sum;
     }
 };
 
@@ -158,7 +298,7 @@ __global__ __launch_bounds__(kSampThreads) void accept_decide_kernel(AcceptArgs 
     const int d_mode = (a.flags & 2u) ? 0 : (a.temperature > 0.f ? 1 : 2);
     __shared__ int s_acc[64];
     __shared__ int s_k;
-    __shared__ unsigned long long tmp[17];
+    __shared__ unsigned long long tmp[kRowVec * 17];
     __shared__ int result;
 
     auto t_row = [&](int j) {
@@ -198,13 +338,41 @@ __global__ __launch_bounds__(kSampThreads) void accept_decide_kernel(AcceptArgs 
     const int k = s_k;
 
     int y;
-    if (k < G) {
-        RowProb T = t_row(k), D = d_row(k);
-        y = sample_inverse_cdf([&](int x) { return fmaxf(0.0f, __fsub_rn(T(x), D(x))); }, V,
-                               a.u[seq * (G + 1) + G], tmp, &result);
-        if (y < 0) y = sample_inverse_cdf(T, V, a.u[seq * (G + 1) + G], tmp, &result);
+    const float u_last = a.u[seq * (G + 1) + G];
+    const RowProb T = t_row(k < G ? k : G);
+    if (row_fits_registers(T.row, V) && (k == G || row_fits_registers(d_row(k).row, V))) {
+        // rows once through registers; padding entries give probability 0 in every mode
+        // (the distribution to draw from, as float32 probabilities, replaces the row in its registers)
+        float4 tv[kRowVec];
+        load_row(T.row, V, T.mode == 0 ? 0.f : -INFINITY, tv);
+        if (k < G) {
+            const RowProb D = d_row(k);
+            float4 dv[kRowVec];
+            load_row(D.row, V, D.mode == 0 ? 0.f : -INFINITY, dv);
+#pragma unroll
+            for (int i = 0; i < kRowVec; ++i) {
+                const int x0 = 4 * (i * kSampThreads + (int)threadIdx.x);
+                tv[i].x = fmaxf(0.0f, __fsub_rn(T.of(tv[i].x, x0), D.of(dv[i].x, x0)));
+                tv[i].y = fmaxf(0.0f, __fsub_rn(T.of(tv[i].y, x0 + 1), D.of(dv[i].y, x0 + 1)));
+                tv[i].z = fmaxf(0.0f, __fsub_rn(T.of(tv[i].z, x0 + 2), D.of(dv[i].z, x0 + 2)));
+                tv[i].w = fmaxf(0.0f, __fsub_rn(T.of(tv[i].w, x0 + 3), D.of(dv[i].w, x0 + 3)));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kRowVec; ++i) {
+                const int x0 = 4 * (i * kSampThreads + (int)threadIdx.x);
+                tv[i] = float4{T.of(tv[i].x, x0), T.of(tv[i].y, x0 + 1), T.of(tv[i].z, x0 + 2), T.of(tv[i].w, x0 + 3)};
+            }
+        }
+        auto elem = [](const float4 &q, int j) { return j == 0 ? q.x : (j == 1 ? q.y : (j == 2 ? q.z : q.w)); };
+        y = sample_inverse_cdf_regs([&](int i, int j, int) { return fixed_weight(elem(tv[i], j)); }, V, u_last, tmp, &result);
+        if (y < 0 && k < G) y = sample_inverse_cdf(T, V, u_last, tmp, &result);   // residual mass truncates to zero: rare
+    } else if (k < G) {
+        const RowProb D = d_row(k);
+        y = sample_inverse_cdf([&](int x) { return fmaxf(0.0f, __fsub_rn(T(x), D(x))); }, V, u_last, tmp, &result);
+        if (y < 0) y = sample_inverse_cdf(T, V, u_last, tmp, &result);
     } else {
-        y = sample_inverse_cdf(t_row(G), V, a.u[seq * (G + 1) + G], tmp, &result);
+        y = sample_inverse_cdf(T, V, u_last, tmp, &result);
     }
     if (threadIdx.x == 0) {
         a.n_accepted[seq] = k;
@@ -240,14 +408,33 @@ __global__ __launch_bounds__(kSampThreads) void softmax_sample_kernel(const floa
     const float *row = logits + (size_t)seq * row_stride;
     float *out = probs_out + (size_t)seq * V;
     __shared__ RowStats st;
-    __shared__ unsigned long long tmp[17];
+    __shared__ unsigned long long tmp[kRowVec * 17];
     __shared__ int result;
     const float inv_temp = temperature > 0.f ? 1.0f / temperature : 1.0f;
-    row_stats(row, V, inv_temp, &st);
     RowProb p;
-    p.row = row; p.st = st; p.inv_temp = inv_temp; p.mode = temperature > 0.f ? 1 : 2;
-    for (int x = threadIdx.x; x < V; x += blockDim.x) out[x] = p(x);
-    int y = sample_inverse_cdf(p, V, u[seq], tmp, &result);
+    p.row = row; p.inv_temp = inv_temp; p.mode = temperature > 0.f ? 1 : 2;
+    int y;
+    if (row_fits_registers(row, V) && row_fits_registers(out, V)) {
+        float4 v[kRowVec];
+        load_row(row, V, -INFINITY, v);
+        row_stats_regs(v, V, inv_temp, &st);
+        p.st = st;
+        const int n4 = V >> 2;
+#pragma unroll
+        for (int i = 0; i < kRowVec; ++i) {
+            const int q = i * kSampThreads + (int)threadIdx.x;
+            const int x0 = 4 * q;
+            v[i] = float4{p.of(v[i].x, x0), p.of(v[i].y, x0 + 1), p.of(v[i].z, x0 + 2), p.of(v[i].w, x0 + 3)};
+            if (q < n4) reinterpret_cast<float4 *>(out)[q] = v[i];
+        }
+        auto elem = [](const float4 &q, int j) { return j == 0 ? q.x : (j == 1 ? q.y : (j == 2 ? q.z : q.w)); };
+        y = sample_inverse_cdf_regs([&](int i, int j, int) { return fixed_weight(elem(v[i], j)); }, V, u[seq], tmp, &result);
+    } else {
+        row_stats(row, V, inv_temp, &st);
+        p.st = st;
+        for (int x = threadIdx.x; x < V; x += blockDim.x) out[x] = p(x);
+        y = sample_inverse_cdf(p, V, u[seq], tmp, &result);
+    }
     if (threadIdx.x == 0) token_out[seq] = y < 0 ? 0 : y;
 }
 
