@@ -15,6 +15,11 @@ constexpr int kSampThreads = 1024;
 
 struct RowStats { float mx; float sum; int argmax; int pad; };
 
+// Numerator of the softmax: exp((l - max) / temp) through the hardware exponential (relative
+// error about |argument| * 6e-8).  Statistics, accept test, residual and the draft's D row all
+// use this one function, so the probabilities of a row are consistent with its sum.
+__device__ __forceinline__ float softmax_num(float l, float mx, float inv_temp) { return __expf((l - mx) * inv_temp); }
+
 __device__ __forceinline__ unsigned long long shfl_up_u64(unsigned long long v, int off) {
     unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
     lo = __shfl_up(lo, off);
@@ -109,7 +114,7 @@ __device__ void row_stats(const float *__restrict__ row, int V, float inv_temp, 
     for (int i = 1; i < nw; ++i)
         if (s_mx[i] > mx || (s_mx[i] == mx && s_arg[i] < arg)) { mx = s_mx[i]; arg = s_arg[i]; }
     float sum = 0.f;
-    for (int x = threadIdx.x; x < V; x += blockDim.x) sum += expf((row[x] - mx) * inv_temp);
+    for (int x = threadIdx.x; x < V; x += blockDim.x) sum += softmax_num(row[x], mx, inv_temp);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
     if (lane == 0) s_sum[w] = sum;
@@ -174,10 +179,10 @@ __device__ void row_stats_regs(const float4 (&v)[kRowVec], int V, float inv_temp
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < kRowVec; ++i) {                       // padding is -inf: exp gives 0
-        sum += expf((v[i].x - mx) * inv_temp);
-        sum += expf((v[i].y - mx) * inv_temp);
-        sum += expf((v[i].z - mx) * inv_temp);
-        sum += expf((v[i].w - mx) * inv_temp);
+        sum += softmax_num(v[i].x, mx, inv_temp);
+        sum += softmax_num(v[i].y, mx, inv_temp);
+        sum += softmax_num(v[i].z, mx, inv_temp);
+        sum += softmax_num(v[i].w, mx, inv_temp);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
@@ -198,16 +203,19 @@ template <class WF>
 __device__ int sample_inverse_cdf_regs(WF wf, int V, float u, unsigned long long *tmp, int *result) {
     // tmp: kRowVec * 17 u64 of shared memory
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    auto part_of = [&](int i) {                               // weights are recomputed rather than kept: registers
+    // The 32 weights of a thread are recomputed where they are needed again instead of being
+    // kept (64 registers).  `salt` is zero, but only at run time, so that the two computations
+    // are not merged back into one long-lived value.
+    auto part_of = [&](int i, unsigned long long salt) {
         const int x0 = 4 * (i * kSampThreads + (int)threadIdx.x);
         unsigned long long p = 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) p += (x0 + j < V) ? wf(i, j, x0 + j) : 0ull;
+        for (int j = 0; j < 4; ++j) p += (x0 + j < V) ? (wf(i, j, x0 + j) ^ salt) : 0ull;
         return p;
     };
     unsigned long long incl[kRowVec];
 #pragma unroll
-    for (int i = 0; i < kRowVec; ++i) incl[i] = part_of(i);
+    for (int i = 0; i < kRowVec; ++i) incl[i] = part_of(i, 0ull);
 #pragma unroll
     for (int i = 0; i < kRowVec; ++i) {
 #pragma unroll
@@ -233,9 +241,10 @@ __device__ int sample_inverse_cdf_regs(WF wf, int V, float u, unsigned long long
     const unsigned long long S = tmp[16];
     if (S != 0) {
         const unsigned long long thr = threshold_of(u, S);
+        const unsigned long long salt = (unsigned long long)(*result + 1);   // result is -1 here
 #pragma unroll
         for (int i = 0; i < kRowVec; ++i) {
-            const unsigned long long part = part_of(i);
+            const unsigned long long part = part_of(i, salt);
             const unsigned long long excl = tmp[i * 17 + w] + incl[i] - part;
             if (excl <= thr && thr < excl + part) {           // exactly one (thread, slice)
                 const int x0 = 4 * (i * kSampThreads + (int)threadIdx.x);
@@ -243,7 +252,7 @@ __device__ int sample_inverse_cdf_regs(WF wf, int V, float u, unsigned long long
                 int found = -1;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    if (x0 + j < V) run += wf(i, j, x0 + j);
+                    if (x0 + j < V) run += wf(i, j, x0 + j) ^ salt;
                     if (found < 0 && run > thr) found = x0 + j;
                 }
                 *result = found;
@@ -279,13 +288,14 @@ struct RowProb {
     const float *row;
     RowStats st;
     float inv_temp;
+    float inv_sum;      // 1 / st.sum (one exact division per row, one multiply per entry)
     int mode;           // 0 probabilities, 1 softmax of logits, 2 greedy one-hot
     __device__ __forceinline__ float operator()(int x) const { return of(row[x], x); }
     // probability of token x whose row entry is `value`
     __device__ __forceinline__ float of(float value, int x) const {
         if (mode == 0) return value;
         if (mode == 2) return x == st.argmax ? 1.0f : 0.0f;
-        return expf((value - st.mx) * inv_temp) / st.sum;
+        return softmax_num(value, st.mx, inv_temp) * inv_sum;
     }
 };
 
@@ -305,14 +315,14 @@ __global__ __launch_bounds__(kSampThreads) void accept_decide_kernel(AcceptArgs 
         RowProb p;
         p.row = a.target + ((size_t)seq * (G + 1) + j) * V;
         p.st = t_mode == 0 ? RowStats{0.f, 1.f, 0, 0} : stats[seq * (G + 1) + j];
-        p.inv_temp = inv_temp; p.mode = t_mode;
+        p.inv_temp = inv_temp; p.mode = t_mode; p.inv_sum = 1.0f / p.st.sum;
         return p;
     };
     auto d_row = [&](int j) {
         RowProb p;
         p.row = a.draft + ((size_t)seq * G + j) * V;
         p.st = d_mode == 0 ? RowStats{0.f, 1.f, 0, 0} : stats[n_t + seq * G + j];
-        p.inv_temp = inv_temp; p.mode = d_mode;
+        p.inv_temp = inv_temp; p.mode = d_mode; p.inv_sum = 1.0f / p.st.sum;
         return p;
     };
 
@@ -418,7 +428,7 @@ __global__ __launch_bounds__(kSampThreads) void softmax_sample_kernel(const floa
         float4 v[kRowVec];
         load_row(row, V, -INFINITY, v);
         row_stats_regs(v, V, inv_temp, &st);
-        p.st = st;
+        p.st = st; p.inv_sum = 1.0f / st.sum;
         const int n4 = V >> 2;
 #pragma unroll
         for (int i = 0; i < kRowVec; ++i) {
@@ -431,7 +441,7 @@ __global__ __launch_bounds__(kSampThreads) void softmax_sample_kernel(const floa
         y = sample_inverse_cdf_regs([&](int i, int j, int) { return fixed_weight(elem(v[i], j)); }, V, u[seq], tmp, &result);
     } else {
         row_stats(row, V, inv_temp, &st);
-        p.st = st;
+        p.st = st; p.inv_sum = 1.0f / st.sum;
         for (int x = threadIdx.x; x < V; x += blockDim.x) out[x] = p(x);
         y = sample_inverse_cdf(p, V, u[seq], tmp, &result);
     }
