@@ -121,7 +121,7 @@ int32_t spd_kv_get_len(const spd_model *model, int32_t *h_len_per_seq, int32_t n
  * e.g. [V_1..V_m ; E[X_1..X_n]] for the target, Section 2.2 Eq. 1) to sequence
  * `seq` starting at its current KV length, appending their K, V.  If
  * last_logits != NULL it receives the float32 logits [vocab] of the last row.
- * Runs the same kernels as the verify step, 8 rows per pass. */
+ * Runs the same kernels as the verify step, 5 rows per pass. */
 int32_t spd_prefill(spd_model *model, int32_t seq, const float *embeds, int32_t n_rows,
                     float *last_logits, void *stream);
 
@@ -182,6 +182,58 @@ int32_t spd_speculative_accept(const float *target, const float *draft, const in
                                int32_t *next_token_out, float *accept_prob_out,
                                void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- the block loop without the host (Section 2.1, one block = gamma draft steps, one
+ * target call, accept / resample, commit) ---------------------------------------------
+ *
+ * With the calls above the host reads k after every block to roll both KV caches back.
+ * The calls below keep the KV lengths in device memory, so that a whole block is a fixed
+ * sequence of launches with fixed arguments: it can be enqueued back to back, or captured
+ * once in a HIP graph and replayed, without a host round trip per block.
+ *
+ * spd_kv_lens_to_device copies the model's current KV lengths into its workspace and
+ * switches the model to device lengths: from then on every forward reads them there and
+ * advances them there.  The host copy becomes an upper bound, so KV overflow can no longer
+ * be refused before the launch: a forward whose device length leaves no room for its rows
+ * works on a clamped length (every access stays in bounds, the results are meaningless) and
+ * raises a flag that spd_kv_lens_from_device reports as SPD_ERR_CAPACITY.  Both calls wait
+ * for `stream` (they are the only ones besides spd_trace_* that block).  spd_kv_set_len is
+ * refused while the lengths live on the device.  The whole-forward persistent kernel is
+ * not used in this mode. */
+int32_t spd_kv_lens_to_device(spd_model *model, void *stream);
+int32_t spd_kv_lens_from_device(spd_model *model, void *stream);
+
+/* spd_draft_step with explicit strides (in elements between consecutive sequences), so that
+ * a draft step can read its input from, and write its token and its D row into, the buffers
+ * the target call and the accept step use: sequence s reads tokens_in[s * in_stride + i]
+ * (i < n_in) and u_draft[s * u_stride], writes D_row_out[s * D_stride + x] (x < vocab) and
+ * token_out[s * token_stride]. */
+int32_t spd_draft_step_strided(spd_model *draft, const int32_t *tokens_in, int32_t in_stride, int32_t n_seqs,
+                               int32_t n_in, float temperature, const float *u_draft, int32_t u_stride,
+                               float *D_row_out, size_t D_stride, int32_t *token_out, int32_t token_stride,
+                               void *stream);
+
+/* Accept / resample and commit of one block, all on the device.  Both models must be in
+ * device-length mode.  Inputs: target_logits float32 [n_seqs, gamma+1, vocab] of the target
+ * call over verify_tokens = [t, d_1..d_gamma] (int32 [n_seqs, gamma+1]); draft_probs float32
+ * [n_seqs, gamma, vocab], the D rows of the draft steps; u as in spd_speculative_accept.
+ * Computes k and y exactly as spd_speculative_accept (target logits, draft probabilities),
+ * then per sequence:
+ *   - appends d_1..d_k, y to out_tokens[s, n_out[s]..] (int32 [n_seqs, out_capacity], may be
+ *     NULL) and adds k+1 to n_out[s] (tokens beyond out_capacity are dropped);
+ *   - verify_tokens[s, 0] = y (the next block's t);
+ *   - draft_in_out[s] = [token before y, y] (int32 [n_seqs, 2]): the next block's first
+ *     draft step takes these two tokens, whether or not the block was fully accepted;
+ *   - both models' KV lengths -= gamma - k.
+ * Convention of the loop: at the start of a block the target's KV cache holds everything
+ * before t and the draft's cache everything before the token that precedes t (so the
+ * draft re-computes that one position each block, which makes every block the same shape);
+ * the first draft step has n_in = 2, the other gamma-1 steps n_in = 1. */
+int32_t spd_block_finish(spd_model *target, spd_model *draft, const float *target_logits, const float *draft_probs,
+                         int32_t *verify_tokens, const float *u, int32_t n_seqs, int32_t gamma, float temperature,
+                         int32_t *n_accepted_out, int32_t *next_token_out, int32_t *draft_in_out,
+                         int32_t *out_tokens, int32_t out_capacity, int32_t *n_out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
 /* Tracing aid (not part of the method).  While enabled, every kernel launch group of
  * this model's forward passes is bracketed by a pair of HIP events on the caller's
  * stream (host-side event objects only: no device memory).  spd_trace_read WAITS for
@@ -189,7 +241,7 @@ int32_t spd_speculative_accept(const float *target, const float *draft, const in
  * milliseconds and launch counts per kind into h_ms_sum[n_kinds] / h_count[n_kinds] and
  * forgets them.  Kinds: 0 QKV projection, 1 O projection, 2 gate|up projection + SwiGLU,
  * 3 down projection, 4 LM head, 5 RoPE + KV append + attention, 6 the whole forward as one
- * persistent kernel (calls of up to 8 rows; kinds 0-5 and 7 then stay empty), 7 input rows
+ * persistent kernel (calls of up to 5 rows; kinds 0-5 and 7 then stay empty), 7 input rows
  * (embedding gather).  The events perturb the stream slightly: time whole
  * steps with tracing off. */
 #define SPD_TRACE_KINDS 8

@@ -61,7 +61,12 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attention_kernel(AttnArgs a) 
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g = lane >> 4;
     const int M = a.Mq, H = a.H;                  // queries of this launch
-    const int P = a.lens.len[seq] + a.m0;         // cached positions before this launch's rows
+    int P0 = a.d_lens ? a.d_lens[seq] : a.lens.len[seq];
+    if (P0 < 0 || P0 + a.M > a.max_positions) {   // only possible with device-resident lengths
+        if (a.d_error && threadIdx.x == 0) *a.d_error = 1;
+        P0 = max(0, min(P0, a.max_positions - a.M));
+    }
+    const int P = P0 + a.m0;                      // cached positions before this launch's rows
     const int row_base = seq * a.M + a.m0;        // first row of this launch in qkv / xout
     const int dim0 = ds * DW;
     const size_t pair = (size_t)seq * H + hh;
@@ -292,7 +297,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attention_kernel(AttnArgs a) 
 
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream) {
     if (a.M < 1 || a.M > 8 || (a.v_stride % 32) != 0 || a.v_stride < a.max_positions) return hipErrorInvalidValue;
-    if (a.Mq < 1 || a.Mq > kGroupRows || a.m0 < 0 || a.m0 + a.Mq > a.M) return hipErrorInvalidValue;
+    if (a.Mq < 1 || a.Mq > kGroupRows || a.m0 < 0 || a.m0 + a.Mq > a.M || a.M > a.max_positions) return hipErrorInvalidValue;
     if (a.dh == 128) {
         hipLaunchKernelGGL((attention_kernel<128, 2>), dim3(2, a.H, a.n_seqs), dim3(kAttnWaves * 64), 0, stream, a);
     } else if (a.dh == 64) {

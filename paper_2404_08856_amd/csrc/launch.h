@@ -47,9 +47,23 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStre
 // Input rows of a forward: h[row, :] = float(E[tokens[row], :]) (token ids clamped into
 // [0, vocab)) or h[row, :] = embeds[row, :]; also writes the packed (h * gain) operand of
 // the first QKV projection and the sum of squares of every row (ssq[row * (d / 16)], one part).
-hipError_t launch_input_rows(const void *embed_bf16, const int32_t *tokens, const float *embeds, int rows,
-                             int d, int vocab, const float *gain, float *h, void *xpack, float *ssq,
-                             hipStream_t stream);
+// tokens: ids of sequence s at tokens[s * token_stride + i], i < M (rows = n_seqs * M).
+hipError_t launch_input_rows(const void *embed_bf16, const int32_t *tokens, int M, int token_stride,
+                             const float *embeds, int rows, int d, int vocab, const float *gain, float *h,
+                             void *xpack, float *ssq, hipStream_t stream);
+// lens[i] += delta for i < n (KV lengths that live on the device)
+hipError_t launch_lens_add(int32_t *lens, int n, int delta, hipStream_t stream);
+// end of a speculative-decoding block, entirely on the device
+struct CommitArgs {
+    const int32_t *n_accepted, *next_token;   // [n_seqs] k and y of the accept step
+    int32_t *verify_tokens;                   // [n_seqs][gamma + 1] in: t, d_1 .. d_gamma; out: slot 0 = y
+    int32_t *draft_in;                        // [n_seqs][2] out: the draft's next inputs (token before y, y)
+    int32_t *target_lens, *draft_lens;        // [n_seqs] device KV lengths, both reduced by gamma - k
+    int32_t *out_tokens;                      // [n_seqs][out_capacity] emitted tokens, or NULL
+    int32_t *n_out;                           // [n_seqs] tokens emitted so far
+    int n_seqs, gamma, out_capacity;
+};
+hipError_t launch_block_commit(const CommitArgs &a, hipStream_t stream);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t stream);
 
 // ---- attention ----------------------------------------------------------------------
@@ -62,6 +76,9 @@ struct AttnArgs {
     int n_seqs, M, H, dh, max_positions, v_stride;
     int m0, Mq;              // this launch handles rows m0 .. m0 + Mq - 1 of every sequence (Mq <= 5); rows
                              // 0 .. m0 - 1 were appended to the cache by an earlier launch
+    const int32_t *d_lens;   // KV lengths in device memory [n_seqs], or NULL: then `lens` below holds them
+    int32_t *d_error;        // set to 1 if a device length does not leave room for M rows (the launch then
+                             // works on a clamped length: wrong results, but every access stays in bounds)
     SeqLens lens;            // KV length of every sequence before this call
 };
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream);
@@ -105,6 +122,7 @@ struct AcceptArgs {
     float temperature;
     uint32_t flags;
     int32_t *n_accepted, *next_token;
+    int token_stride;        // draft token j of sequence s at draft_tokens[s * token_stride + j]
     float *accept_prob;      // may be NULL
     float *stats;            // workspace: [n_seqs * (2 gamma + 1), 4]
 };
@@ -112,8 +130,9 @@ hipError_t launch_accept(const AcceptArgs &a, hipStream_t stream);
 size_t accept_workspace_bytes(int n_seqs, int gamma);
 
 // softmax(logits[seq * ld_rows + ...]) -> probs row + one sample per sequence
+// sequence s: logits + s * row_stride, u[s * u_stride], probs_out + s * probs_stride, token_out[s * token_stride]
 hipError_t launch_softmax_sample(const float *logits, size_t row_stride, int n_seqs, int vocab,
-                                 float temperature, const float *u, float *probs_out,
-                                 int32_t *token_out, hipStream_t stream);
+                                 float temperature, const float *u, int u_stride, float *probs_out,
+                                 size_t probs_stride, int32_t *token_out, int token_stride, hipStream_t stream);
 
 }  // namespace spd

@@ -49,7 +49,7 @@ struct Layout {                    // byte offsets inside the three buffers
     size_t kv_layer_stride, kv_k_bytes, kv_v_bytes, kv_total;
     int v_stride;
     // workspace
-    size_t h, qkv, xn, xo, xf, rope, logits, ssq_a, ssq_b, ws_total;
+    size_t h, qkv, xn, xo, xf, rope, logits, ssq_a, ssq_b, d_lens, d_error, ws_total;
     size_t m_hg, m_att, m_xf, m_ssq_a, m_ssq_b, m_sync, m_clock;     // arrays of the whole-forward kernel (8 rows)
 };
 
@@ -101,6 +101,8 @@ void make_layout(const spd_model_config &c, Layout &L) {
     L.xf = take((size_t)kMaxGroups * KSf * 1024);
     L.rope = take((size_t)c.max_positions * (c.head_dim / 2) * 2 * 4);
     L.logits = take((size_t)kMaxRows * V * 4);
+    L.d_lens = take((size_t)kMaxRows * 4);
+    L.d_error = take(4);
     L.ssq_a = take((size_t)(d / 16) * kMaxRows * 4);
     L.ssq_b = take((size_t)(d / 16) * kMaxRows * 4);
     L.m_hg = take((size_t)8 * d * 4);
@@ -156,7 +158,8 @@ struct spd_model {
     spd_model_config cfg;
     Layout L;
     char *packed, *kv, *ws;
-    std::vector<int32_t> lens;
+    std::vector<int32_t> lens;         // KV lengths (host).  With dev_lens: only an upper bound
+    bool dev_lens = false;             // the kernels read the lengths from device memory (ws + L.d_lens)
     std::vector<float> rope_host;
     GemmTuning t_qkv, t_o, t_gu, t_down, t_lm;
     int mega_grid = 0;                 // workgroups of the whole-forward kernel (0: not available)
@@ -310,7 +313,31 @@ int32_t spd_kv_set_len(spd_model *m, const int32_t *len, int32_t n_seqs) {
         if (len[i] < 0) return fail(SPD_ERR_INVALID_ARG, "negative KV length");
         if (len[i] > m->cfg.max_positions) return fail(SPD_ERR_CAPACITY, "KV length %d exceeds max_positions %d", len[i], m->cfg.max_positions);
     }
+    if (m->dev_lens) return fail(SPD_ERR_INVALID_ARG, "KV lengths live on the device: call spd_kv_lens_from_device first");
     for (int i = 0; i < n_seqs; ++i) m->lens[i] = len[i];
+    return SPD_OK;
+}
+
+int32_t spd_kv_lens_to_device(spd_model *m, void *stream) {
+    if (!m) return fail(SPD_ERR_INVALID_ARG, "NULL model");
+    HIP_TRY(hipMemcpyAsync(m->ws + m->L.d_lens, m->lens.data(), (size_t)m->cfg.max_seqs * 4, hipMemcpyHostToDevice, (hipStream_t)stream));
+    HIP_TRY(launch_fill_zero(m->ws + m->L.d_error, 16, (hipStream_t)stream));
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));          // the host array may change right after this call
+    m->dev_lens = true;
+    return SPD_OK;
+}
+
+int32_t spd_kv_lens_from_device(spd_model *m, void *stream) {
+    if (!m) return fail(SPD_ERR_INVALID_ARG, "NULL model");
+    if (!m->dev_lens) return SPD_OK;
+    std::vector<int32_t> tmp((size_t)m->cfg.max_seqs + 1);
+    HIP_TRY(hipMemcpyAsync(tmp.data(), m->ws + m->L.d_lens, (size_t)m->cfg.max_seqs * 4, hipMemcpyDeviceToHost, (hipStream_t)stream));
+    HIP_TRY(hipMemcpyAsync(&tmp[m->cfg.max_seqs], m->ws + m->L.d_error, 4, hipMemcpyDeviceToHost, (hipStream_t)stream));
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    m->dev_lens = false;
+    const bool overflow = tmp[m->cfg.max_seqs] != 0;
+    for (int i = 0; i < m->cfg.max_seqs; ++i) m->lens[i] = std::max(0, std::min(tmp[i], m->cfg.max_positions));
+    if (overflow) return fail(SPD_ERR_CAPACITY, "a forward ran with a device KV length that left no room for its rows");
     return SPD_OK;
 }
 
@@ -327,7 +354,7 @@ namespace {
 
 // One decoder forward over M new rows for sequences seq0 .. seq0 + n_seqs - 1.
 // Input rows come from token ids (embedding gather) or from embedding rows.
-int32_t forward(spd_model *m, const int32_t *tokens, const float *embeds, int seq0, int n_seqs, int M,
+int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const float *embeds, int seq0, int n_seqs, int M,
                 float *logits_out, hipStream_t st) {
     const spd_model_config &c = m->cfg;
     const Layout &L = m->L;
@@ -335,17 +362,22 @@ int32_t forward(spd_model *m, const int32_t *tokens, const float *embeds, int se
     if (M < 1 || M > SPD_MAX_M) return fail(SPD_ERR_SHAPE, "M = %d must be in 1..%d", M, SPD_MAX_M);
     if (n_seqs < 1 || rows > SPD_MAX_ROWS) return fail(SPD_ERR_SHAPE, "n_seqs * M = %d must be in 1..%d", rows, SPD_MAX_ROWS);
     if (seq0 < 0 || seq0 + n_seqs > c.max_seqs) return fail(SPD_ERR_CAPACITY, "sequence index beyond max_seqs %d", c.max_seqs);
-    int max_total = 0;
-    AttnArgs at;
+    if (M > c.max_positions) return fail(SPD_ERR_CAPACITY, "M = %d exceeds max_positions %d", M, c.max_positions);
+    if (tokens && token_stride < M) return fail(SPD_ERR_INVALID_ARG, "token stride %d below M = %d", token_stride, M);
+    AttnArgs at{};
     for (int s = 0; s < n_seqs; ++s) {
         int len = m->lens[seq0 + s];
-        if (len + M > c.max_positions)
+        // lengths on the device: the host value is an upper bound and the kernels guard themselves
+        if (!m->dev_lens && len + M > c.max_positions)
             return fail(SPD_ERR_CAPACITY, "KV cache overflow: sequence %d has %d positions, +%d > %d", seq0 + s, len, M, c.max_positions);
         at.lens.len[s] = len;
-        if (len + M > max_total) max_total = len + M;
+    }
+    if (m->dev_lens) {
+        at.d_lens = (const int32_t *)(m->ws + L.d_lens) + seq0;
+        at.d_error = (int32_t *)(m->ws + L.d_error);
     }
     const int d = c.d_model, HD = c.n_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
-    if (rows <= kGroupRows && m->mega_grid > 0) {
+    if (rows <= kGroupRows && m->mega_grid > 0 && !m->dev_lens) {
         MegaArgs ma{};
         ma.packed = m->packed;
         ma.off_embed = L.embed; ma.off_lm_head = L.lm_head; ma.off_final_norm = L.final_norm;
@@ -379,8 +411,8 @@ int32_t forward(spd_model *m, const int32_t *tokens, const float *embeds, int se
     auto gain_of = [&](size_t off) { return (const float *)(m->packed + off); };
 
     // input rows -> h, packed (h * attn_norm[0]) and sum of squares (one part per row)
-    PROF_TRY(PK_EMBED, launch_input_rows(m->packed + L.embed, tokens, embeds, rows, d, V, gain_of(L.attn_norm[0]),
-                                         h, xn, ssq_b, st));
+    PROF_TRY(PK_EMBED, launch_input_rows(m->packed + L.embed, tokens, M, tokens ? token_stride : M, embeds, rows, d, V,
+                                         gain_of(L.attn_norm[0]), h, xn, ssq_b, st));
 
     at.qkv = qkv;
     at.rope = (const float *)(m->ws + L.rope);
@@ -422,7 +454,8 @@ int32_t forward(spd_model *m, const int32_t *tokens, const float *embeds, int se
         g.ssq_in = ssq_b; g.ssq_in_parts = d_tiles; g.eps = c.rms_eps;
         PROF_TRY(PK_LM_HEAD, launch_gemm(g, EPI_STORE, m->t_lm, st));
     }
-    for (int s = 0; s < n_seqs; ++s) m->lens[seq0 + s] += M;
+    if (m->dev_lens) HIP_TRY(launch_lens_add((int32_t *)(m->ws + L.d_lens) + seq0, n_seqs, M, st));
+    for (int s = 0; s < n_seqs; ++s) m->lens[seq0 + s] = std::min(m->lens[seq0 + s] + M, c.max_positions);
     return SPD_OK;
 }
 
@@ -437,7 +470,7 @@ int32_t prefill_common(spd_model *m, int32_t seq, const float *embeds, const int
     for (int r0 = 0; r0 < n_rows; r0 += kGroupRows) {        // one row group per pass: the single-group kernels
         int M = n_rows - r0 < kGroupRows ? n_rows - r0 : kGroupRows;
         bool last = r0 + M >= n_rows;
-        int32_t rc = forward(m, tokens ? tokens + r0 : nullptr, embeds ? embeds + (size_t)r0 * m->cfg.d_model : nullptr,
+        int32_t rc = forward(m, tokens ? tokens + r0 : nullptr, M, embeds ? embeds + (size_t)r0 * m->cfg.d_model : nullptr,
                              seq, 1, M, (last && last_logits) ? scratch : nullptr, st);
         if (rc) return rc;
         if (last && last_logits)
@@ -509,21 +542,31 @@ int32_t spd_prefill_tokens(spd_model *m, int32_t seq, const int32_t *tokens, int
 
 int32_t spd_verify_forward(spd_model *m, const int32_t *tokens, int32_t n_seqs, int32_t M, float *logits_out, void *stream) {
     if (!m || !tokens || !logits_out) return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_verify_forward");
-    return forward(m, tokens, nullptr, 0, n_seqs, M, logits_out, (hipStream_t)stream);
+    return forward(m, tokens, M, nullptr, 0, n_seqs, M, logits_out, (hipStream_t)stream);
+}
+
+int32_t spd_draft_step_strided(spd_model *m, const int32_t *tokens_in, int32_t in_stride, int32_t n_seqs, int32_t n_in,
+                               float temperature, const float *u_draft, int32_t u_stride, float *D_row_out,
+                               size_t D_stride, int32_t *token_out, int32_t token_stride, void *stream) {
+    if (!m || !tokens_in || !u_draft || !D_row_out || !token_out) return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_draft_step");
+    if (n_in < 1 || n_in > 2) return fail(SPD_ERR_SHAPE, "n_in = %d must be 1 or 2", n_in);
+    if (!(temperature >= 0.f)) return fail(SPD_ERR_INVALID_ARG, "temperature must be >= 0");
+    if (in_stride < n_in || u_stride < 1 || token_stride < 1 || D_stride < (size_t)m->cfg.vocab)
+        return fail(SPD_ERR_INVALID_ARG, "strides must cover one sequence's entries");
+    float *scratch = (float *)(m->ws + m->L.logits);
+    int32_t rc = forward(m, tokens_in, in_stride, nullptr, 0, n_seqs, n_in, scratch, (hipStream_t)stream);
+    if (rc) return rc;
+    const size_t V = m->cfg.vocab;
+    HIP_TRY(launch_softmax_sample(scratch + (size_t)(n_in - 1) * V, (size_t)n_in * V, n_seqs, (int)V, temperature,
+                                  u_draft, u_stride, D_row_out, D_stride, token_out, token_stride, (hipStream_t)stream));
+    return SPD_OK;
 }
 
 int32_t spd_draft_step(spd_model *m, const int32_t *tokens_in, int32_t n_seqs, int32_t n_in, float temperature,
                        const float *u_draft, float *D_row_out, int32_t *token_out, void *stream) {
-    if (!m || !tokens_in || !u_draft || !D_row_out || !token_out) return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_draft_step");
-    if (n_in < 1 || n_in > 2) return fail(SPD_ERR_SHAPE, "n_in = %d must be 1 or 2", n_in);
-    if (!(temperature >= 0.f)) return fail(SPD_ERR_INVALID_ARG, "temperature must be >= 0");
-    float *scratch = (float *)(m->ws + m->L.logits);
-    int32_t rc = forward(m, tokens_in, nullptr, 0, n_seqs, n_in, scratch, (hipStream_t)stream);
-    if (rc) return rc;
-    const size_t V = m->cfg.vocab;
-    HIP_TRY(launch_softmax_sample(scratch + (size_t)(n_in - 1) * V, (size_t)n_in * V, n_seqs, (int)V, temperature,
-                                  u_draft, D_row_out, token_out, (hipStream_t)stream));
-    return SPD_OK;
+    if (!m) return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_draft_step");
+    return spd_draft_step_strided(m, tokens_in, n_in, n_seqs, n_in, temperature, u_draft, 1, D_row_out,
+                                  (size_t)m->cfg.vocab, token_out, 1, stream);
 }
 
 int32_t spd_accept_workspace_bytes(int32_t n_seqs, int32_t gamma, int32_t vocab, size_t *bytes) {
@@ -546,8 +589,39 @@ int32_t spd_speculative_accept(const float *target, const float *draft, const in
     a.target = target; a.draft = draft; a.draft_tokens = draft_tokens; a.u = u;
     a.n_seqs = n_seqs; a.gamma = gamma; a.vocab = vocab; a.temperature = temperature; a.flags = flags;
     a.n_accepted = n_accepted_out; a.next_token = next_token_out; a.accept_prob = accept_prob_out;
+    a.token_stride = gamma;
     a.stats = (float *)workspace;
     HIP_TRY(launch_accept(a, (hipStream_t)stream));
+    return SPD_OK;
+}
+
+int32_t spd_block_finish(spd_model *target, spd_model *draft, const float *target_logits, const float *draft_probs,
+                         int32_t *verify_tokens, const float *u, int32_t n_seqs, int32_t gamma, float temperature,
+                         int32_t *n_accepted_out, int32_t *next_token_out, int32_t *draft_in_out, int32_t *out_tokens,
+                         int32_t out_capacity, int32_t *n_out, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!target || !draft || !target_logits || !draft_probs || !verify_tokens || !u || !n_accepted_out || !next_token_out ||
+        !draft_in_out || !workspace || (out_tokens && !n_out))
+        return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_block_finish");
+    if (!target->dev_lens || !draft->dev_lens)
+        return fail(SPD_ERR_INVALID_ARG, "spd_block_finish needs both models' KV lengths on the device (spd_kv_lens_to_device)");
+    if (n_seqs < 1 || n_seqs > target->cfg.max_seqs || n_seqs > draft->cfg.max_seqs) return fail(SPD_ERR_CAPACITY, "n_seqs exceeds max_seqs");
+    if (gamma < 1 || gamma + 1 > SPD_MAX_M) return fail(SPD_ERR_SHAPE, "gamma + 1 must be in 2..%d", SPD_MAX_M);
+    if (target->cfg.vocab != draft->cfg.vocab) return fail(SPD_ERR_SHAPE, "target and draft vocabularies differ");
+    if (!(temperature >= 0.f)) return fail(SPD_ERR_INVALID_ARG, "temperature must be >= 0");
+    if (out_tokens && out_capacity < 1) return fail(SPD_ERR_INVALID_ARG, "out_capacity must be positive");
+    if (workspace_bytes < accept_workspace_bytes(n_seqs, gamma)) return fail(SPD_ERR_CAPACITY, "accept workspace too small");
+    AcceptArgs a;
+    a.target = target_logits; a.draft = draft_probs; a.draft_tokens = verify_tokens + 1; a.token_stride = gamma + 1; a.u = u;
+    a.n_seqs = n_seqs; a.gamma = gamma; a.vocab = target->cfg.vocab; a.temperature = temperature; a.flags = SPD_DRAFT_IS_PROBS;
+    a.n_accepted = n_accepted_out; a.next_token = next_token_out; a.accept_prob = nullptr;
+    a.stats = (float *)workspace;
+    HIP_TRY(launch_accept(a, (hipStream_t)stream));
+    CommitArgs cm;
+    cm.n_accepted = n_accepted_out; cm.next_token = next_token_out; cm.verify_tokens = verify_tokens; cm.draft_in = draft_in_out;
+    cm.target_lens = (int32_t *)(target->ws + target->L.d_lens); cm.draft_lens = (int32_t *)(draft->ws + draft->L.d_lens);
+    cm.out_tokens = out_tokens; cm.n_out = n_out; cm.n_seqs = n_seqs; cm.gamma = gamma; cm.out_capacity = out_capacity;
+    HIP_TRY(launch_block_commit(cm, (hipStream_t)stream));
+    // host bounds: at most gamma + 1 positions per sequence were added by the verify call and stay
     return SPD_OK;
 }
 

@@ -8,7 +8,7 @@ namespace spd {
 // operand of (h * gain) for the first QKV projection, and sum(h^2) of the row
 // (the RMSNorm scale itself is applied inside that projection).
 __global__ __launch_bounds__(256) void input_rows_kernel(const uint16_t *__restrict__ E,
-                                                         const int32_t *__restrict__ tokens,
+                                                         const int32_t *__restrict__ tokens, int M, int token_stride,
                                                          const float *__restrict__ embeds, int d, int vocab,
                                                          const float *__restrict__ gain, float *__restrict__ h,
                                                          uint16_t *__restrict__ xpack, float *__restrict__ ssq) {
@@ -16,7 +16,9 @@ __global__ __launch_bounds__(256) void input_rows_kernel(const uint16_t *__restr
     const int KS = d / 32;
     const uint16_t *src_tok = nullptr;
     if (tokens) {
-        int tok = min(max(tokens[row], 0), vocab - 1);                // never read outside the table
+        // row = seq * M + i; the ids of one sequence are token_stride apart from the next one's
+        int tok = tokens[(size_t)(row / M) * token_stride + row % M];
+        tok = min(max(tok, 0), vocab - 1);                            // never read outside the table
         src_tok = E + (size_t)tok * d;
     }
     const float *src_row = embeds ? embeds + (size_t)row * d : nullptr;
@@ -54,12 +56,52 @@ __global__ __launch_bounds__(256) void input_rows_kernel(const uint16_t *__restr
     if (threadIdx.x == 0) ssq[(size_t)row * (d / 16)] = (part[0] + part[1]) + (part[2] + part[3]);   // part 0 of [rows][d / 16]
 }
 
-hipError_t launch_input_rows(const void *embed_bf16, const int32_t *tokens, const float *embeds, int rows,
-                             int d, int vocab, const float *gain, float *h, void *xpack, float *ssq,
-                             hipStream_t stream) {
-    if ((!tokens) == (!embeds)) return hipErrorInvalidValue;
+hipError_t launch_input_rows(const void *embed_bf16, const int32_t *tokens, int M, int token_stride,
+                             const float *embeds, int rows, int d, int vocab, const float *gain, float *h,
+                             void *xpack, float *ssq, hipStream_t stream) {
+    if ((!tokens) == (!embeds) || M < 1 || token_stride < M) return hipErrorInvalidValue;
     hipLaunchKernelGGL(input_rows_kernel, dim3(rows), dim3(256), 0, stream, (const uint16_t *)embed_bf16,
-                       tokens, embeds, d, vocab, gain, h, (uint16_t *)xpack, ssq);
+                       tokens, M, token_stride, embeds, d, vocab, gain, h, (uint16_t *)xpack, ssq);
+    return hipGetLastError();
+}
+
+// ---- KV lengths kept on the device ---------------------------------------------------------
+__global__ void lens_add_kernel(int32_t *lens, int n, int delta) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) lens[i] += delta;
+}
+
+hipError_t launch_lens_add(int32_t *lens, int n, int delta, hipStream_t stream) {
+    hipLaunchKernelGGL(lens_add_kernel, dim3((n + 63) / 64), dim3(64), 0, stream, lens, n, delta);
+    return hipGetLastError();
+}
+
+// End of a speculative-decoding block, one thread per sequence: emit d_1 .. d_k and y, make y the
+// first token of the next verify call, hand the draft its next two inputs and roll both KV
+// lengths back by the gamma - k rejected positions.
+__global__ void block_commit_kernel(CommitArgs a) {
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= a.n_seqs) return;
+    const int G = a.gamma;
+    const int k = min(max(a.n_accepted[s], 0), G);
+    const int y = a.next_token[s];
+    int32_t *vt = a.verify_tokens + (size_t)s * (G + 1);
+    if (a.out_tokens) {
+        int n = a.n_out[s];
+        for (int j = 0; j <= k; ++j)
+            if (n + j < a.out_capacity) a.out_tokens[(size_t)s * a.out_capacity + n + j] = (j < k) ? vt[1 + j] : y;
+        a.n_out[s] = min(n + k + 1, a.out_capacity);
+    }
+    a.draft_in[2 * s + 0] = vt[k];             // token before y: d_k, or t when nothing was accepted
+    a.draft_in[2 * s + 1] = y;
+    vt[0] = y;
+    a.target_lens[s] -= G - k;
+    a.draft_lens[s] -= G - k;
+}
+
+hipError_t launch_block_commit(const CommitArgs &a, hipStream_t stream) {
+    if (a.n_seqs < 1 || a.gamma < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(block_commit_kernel, dim3((a.n_seqs + 63) / 64), dim3(64), 0, stream, a);
     return hipGetLastError();
 }
 

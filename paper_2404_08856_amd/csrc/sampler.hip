@@ -329,7 +329,7 @@ __global__ __launch_bounds__(kSampThreads) void accept_decide_kernel(AcceptArgs 
     // accept tests: u_j * D_j(d_j) < T_j(d_j), one float32 multiply and one compare
     if ((int)threadIdx.x < G) {
         int j = threadIdx.x;
-        int d = min(max(a.draft_tokens[seq * G + j], 0), V - 1);   // never index outside the row
+        int d = min(max(a.draft_tokens[(size_t)seq * a.token_stride + j], 0), V - 1);   // never index outside the row
         float Tx = t_row(j)(d), Dx = d_row(j)(d);
         float u = a.u[seq * (G + 1) + j];
         s_acc[j] = (__fmul_rn(u, Dx) < Tx) ? 1 : 0;
@@ -411,12 +411,13 @@ hipError_t launch_accept(const AcceptArgs &a, hipStream_t stream) {
 __global__ __launch_bounds__(kSampThreads) void softmax_sample_kernel(const float *__restrict__ logits,
                                                                        size_t row_stride, int V,
                                                                        float temperature,
-                                                                       const float *__restrict__ u,
-                                                                       float *__restrict__ probs_out,
-                                                                       int32_t *__restrict__ token_out) {
+                                                                       const float *__restrict__ u, int u_stride,
+                                                                       float *__restrict__ probs_out, size_t probs_stride,
+                                                                       int32_t *__restrict__ token_out, int token_stride) {
     const int seq = blockIdx.x;
     const float *row = logits + (size_t)seq * row_stride;
-    float *out = probs_out + (size_t)seq * V;
+    float *out = probs_out + (size_t)seq * probs_stride;
+    const float u_seq = u[(size_t)seq * u_stride];
     __shared__ RowStats st;
     __shared__ unsigned long long tmp[kRowVec * 17];
     __shared__ int result;
@@ -438,21 +439,21 @@ __global__ __launch_bounds__(kSampThreads) void softmax_sample_kernel(const floa
             if (q < n4) reinterpret_cast<float4 *>(out)[q] = v[i];
         }
         auto elem = [](const float4 &q, int j) { return j == 0 ? q.x : (j == 1 ? q.y : (j == 2 ? q.z : q.w)); };
-        y = sample_inverse_cdf_regs([&](int i, int j, int) { return fixed_weight(elem(v[i], j)); }, V, u[seq], tmp, &result);
+        y = sample_inverse_cdf_regs([&](int i, int j, int) { return fixed_weight(elem(v[i], j)); }, V, u_seq, tmp, &result);
     } else {
         row_stats(row, V, inv_temp, &st);
         p.st = st; p.inv_sum = 1.0f / st.sum;
         for (int x = threadIdx.x; x < V; x += blockDim.x) out[x] = p(x);
-        y = sample_inverse_cdf(p, V, u[seq], tmp, &result);
+        y = sample_inverse_cdf(p, V, u_seq, tmp, &result);
     }
-    if (threadIdx.x == 0) token_out[seq] = y < 0 ? 0 : y;
+    if (threadIdx.x == 0) token_out[(size_t)seq * token_stride] = y < 0 ? 0 : y;
 }
 
 hipError_t launch_softmax_sample(const float *logits, size_t row_stride, int n_seqs, int vocab,
-                                 float temperature, const float *u, float *probs_out,
-                                 int32_t *token_out, hipStream_t stream) {
+                                 float temperature, const float *u, int u_stride, float *probs_out,
+                                 size_t probs_stride, int32_t *token_out, int token_stride, hipStream_t stream) {
     hipLaunchKernelGGL(softmax_sample_kernel, dim3(n_seqs), dim3(kSampThreads), 0, stream, logits,
-                       row_stride, vocab, temperature, u, probs_out, token_out);
+                       row_stride, vocab, temperature, u, u_stride, probs_out, probs_stride, token_out, token_stride);
     return hipGetLastError();
 }
 

@@ -25,7 +25,8 @@ SPD_MAX_ROWS, SPD_MAX_M = 64, 8
 EXPORTS = ["spd_last_error", "spd_model_bytes", "spd_model_create", "spd_model_destroy", "spd_kv_set_len",
            "spd_kv_get_len", "spd_prefill", "spd_prefill_tokens", "spd_verify_forward", "spd_draft_step",
            "spd_accept_workspace_bytes", "spd_speculative_accept", "spd_trace_enable", "spd_trace_read",
-           "spd_trace_stages"]
+           "spd_trace_stages", "spd_kv_lens_to_device", "spd_kv_lens_from_device", "spd_draft_step_strided",
+           "spd_block_finish"]
 TRACE_KINDS = ["qkv", "o", "gate_up", "down", "lm_head", "attention", "forward", "embed"]
 
 
@@ -71,6 +72,10 @@ _lib.spd_speculative_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _f
 _lib.spd_trace_enable.argtypes = [_vp, _i32]
 _lib.spd_trace_read.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i32)]
 _lib.spd_trace_stages.argtypes = [_vp, _i32] + [ctypes.POINTER(ctypes.c_double)] * 4 + [ctypes.POINTER(_i32)]
+_lib.spd_kv_lens_to_device.argtypes = [_vp, _vp]
+_lib.spd_kv_lens_from_device.argtypes = [_vp, _vp]
+_lib.spd_draft_step_strided.argtypes = [_vp, _vp, _i32, _i32, _i32, _f32, _vp, _i32, _vp, _sz, _vp, _i32, _vp]
+_lib.spd_block_finish.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
 for _name in EXPORTS:
     if _name != "spd_last_error":
         getattr(_lib, _name).restype = _i32
@@ -95,6 +100,12 @@ def _ptr(t, dtype=None):
     assert t.is_cuda and t.is_contiguous(), "device, contiguous tensors only"
     if dtype is not None:
         assert t.dtype == dtype, f"expected {dtype}, got {t.dtype}"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _raw(t, dtype):
+    """Data pointer of a device tensor that may be a strided view into a larger buffer."""
+    assert t.is_cuda and t.dtype == dtype
     return ctypes.c_void_p(t.data_ptr())
 
 
@@ -181,6 +192,21 @@ class Model:
                                    _ptr(token_out, torch.int32), _stream()))
 
 
+    def spd_draft_step_strided(self, tokens_in, in_stride, n_seqs, n_in, temperature, u_draft, u_stride,
+                               D_row_out, D_stride, token_out, token_stride):
+        """tokens_in, u_draft, D_row_out, token_out: device tensors (views into larger buffers are fine:
+        only their data pointers are used; the strides are in elements between sequences)."""
+        _check(_lib.spd_draft_step_strided(self.handle, _raw(tokens_in, torch.int32), in_stride, n_seqs, n_in,
+                                           float(temperature), _raw(u_draft, torch.float32), u_stride,
+                                           _raw(D_row_out, torch.float32), D_stride, _raw(token_out, torch.int32),
+                                           token_stride, _stream()))
+
+    def spd_kv_lens_to_device(self):
+        _check(_lib.spd_kv_lens_to_device(self.handle, _stream()))
+
+    def spd_kv_lens_from_device(self):
+        _check(_lib.spd_kv_lens_from_device(self.handle, _stream()))
+
     def spd_trace_enable(self, enable):
         _check(_lib.spd_trace_enable(self.handle, int(bool(enable))))
 
@@ -199,6 +225,23 @@ class Model:
         cnt = (ctypes.c_int32 * n)()
         _check(_lib.spd_trace_read(self.handle, n, ms, cnt))
         return {k: (ms[i], cnt[i]) for i, k in enumerate(TRACE_KINDS)}
+
+
+def spd_block_finish(target, draft, target_logits, draft_probs, verify_tokens, u, temperature, n_accepted_out,
+                     next_token_out, draft_in_out, out_tokens=None, n_out=None, workspace=None):
+    n_seqs, g1, vocab = target_logits.shape
+    gamma = g1 - 1
+    assert draft_probs.shape == (n_seqs, gamma, vocab) and verify_tokens.shape == (n_seqs, g1) and u.shape == (n_seqs, g1)
+    assert draft_in_out.shape == (n_seqs, 2)
+    if workspace is None:
+        workspace = torch.empty(spd_accept_workspace_bytes(n_seqs, gamma, vocab), dtype=torch.uint8, device=target_logits.device)
+    cap = 0 if out_tokens is None else out_tokens.shape[1]
+    _check(_lib.spd_block_finish(target.handle, draft.handle, _ptr(target_logits, torch.float32), _ptr(draft_probs, torch.float32),
+                                 _ptr(verify_tokens, torch.int32), _ptr(u, torch.float32), n_seqs, gamma, float(temperature),
+                                 _ptr(n_accepted_out, torch.int32), _ptr(next_token_out, torch.int32),
+                                 _ptr(draft_in_out, torch.int32), _ptr(out_tokens, torch.int32), cap, _ptr(n_out, torch.int32),
+                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+    return workspace
 
 
 def spd_accept_workspace_bytes(n_seqs, gamma, vocab):

@@ -181,3 +181,195 @@ def test_block_loop_greedy_equals_autoregressive_on_device():
     first_unsafe = next((i for i, mg in enumerate(margins) if mg < 1e-3), len(margins))
     assert out[:first_unsafe + 1] == ar[:first_unsafe + 1]
     assert first_unsafe >= len(margins) // 2
+
+
+# ---------------------------------------------------------------------------------------------
+# the block loop with KV lengths, tokens and the commit kept on the device
+# ---------------------------------------------------------------------------------------------
+class DeviceLoop:
+    """Buffers and the fixed launch sequence of one block (what a HIP graph captures)."""
+
+    def __init__(self, target, draft, n_seqs, gamma, V, temperature, out_cap):
+        self.spd = spd_mod()
+        self.target, self.draft, self.n_seqs, self.gamma, self.V, self.temperature = target, draft, n_seqs, gamma, V, temperature
+        dev = "cuda"
+        self.vt = torch.zeros((n_seqs, gamma + 1), dtype=torch.int32, device=dev)        # t, d_1 .. d_gamma
+        self.din = torch.zeros((n_seqs, 2), dtype=torch.int32, device=dev)               # draft's first inputs
+        self.D = torch.zeros((n_seqs, gamma, V), dtype=torch.float32, device=dev)
+        self.logits = torch.zeros((n_seqs, gamma + 1, V), dtype=torch.float32, device=dev)
+        self.u_draft = torch.zeros((n_seqs, gamma), dtype=torch.float32, device=dev)     # this block's uniforms (staging)
+        self.u_accept = torch.zeros((n_seqs, gamma + 1), dtype=torch.float32, device=dev)
+        self.k = torch.zeros((n_seqs,), dtype=torch.int32, device=dev)
+        self.y = torch.zeros((n_seqs,), dtype=torch.int32, device=dev)
+        self.out = torch.zeros((n_seqs, out_cap), dtype=torch.int32, device=dev)
+        self.n_out = torch.zeros((n_seqs,), dtype=torch.int32, device=dev)
+        self.ws = torch.empty(self.spd.spd_accept_workspace_bytes(n_seqs, gamma, V), dtype=torch.uint8, device=dev)
+
+    def block(self):
+        g, V, n = self.gamma, self.V, self.n_seqs
+        vt_flat, D_flat, u_flat = self.vt.view(-1), self.D.view(-1), self.u_draft.view(-1)
+        self.draft.spd_draft_step_strided(self.din, 2, n, 2, self.temperature, u_flat, g, D_flat, g * V, vt_flat[1:], g + 1)
+        for j in range(1, g):
+            self.draft.spd_draft_step_strided(vt_flat[j:], g + 1, n, 1, self.temperature, u_flat[j:], g,
+                                              D_flat[j * V:], g * V, vt_flat[j + 1:], g + 1)
+        self.target.spd_verify_forward(self.vt, self.logits)
+        self.spd.spd_block_finish(self.target, self.draft, self.logits, self.D, self.vt, self.u_accept, self.temperature,
+                                  self.k, self.y, self.din, self.out, self.n_out, self.ws)
+
+
+def setup_device_loop(n_seqs, gamma, n_blocks, temperature, seed, m_img):
+    """Prefill target ([image ; text]) and draft (text) for n_seqs ragged prompts, on device and in the oracle."""
+    spd = spd_mod()
+    t_shape, d_shape = synth.SHAPES["tiny_target"], synth.SHAPES["tiny_draft"]
+    V = t_shape.vocab
+    cap = m_img + 40 + n_blocks * (gamma + 1) + 8
+    tw = randomize_gains(synth.make_weights(t_shape, seed))
+    dw = randomize_gains(synth.make_weights(d_shape, seed + 50), seed=5)
+    target = spd.Model(spd.make_config(t_shape, n_seqs, cap), to_device(tw))
+    draft = spd.Model(spd.make_config(d_shape, n_seqs, cap), to_device(dw))
+    twn, dwn = synth.weights_to_numpy(tw), synth.weights_to_numpy(dw)
+    tc, dc = oracle_cfg(t_shape), oracle_cfg(d_shape)
+    loop = DeviceLoop(target, draft, n_seqs, gamma, V, temperature, n_blocks * (gamma + 1))
+    oracle = []
+    u_first = synth.uniforms((n_seqs,), seed + 1)
+    for s in range(n_seqs):
+        n_text = 12 + 9 * s
+        toks = synth.text_tokens(n_text, V, seed + s)
+        x = np.concatenate([synth.image_rows(m_img, t_shape.d_model, seed + s).astype(np.float64), dec.embed_tokens(twn, toks)])
+        t_cache, d_cache = dec.KVCache(tc, cap), dec.KVCache(dc, cap)
+        ref_last = dec.forward_rows(tc, twn, t_cache, x)[-1]
+        dec.forward_tokens(dc, dwn, d_cache, toks)
+        last = torch.empty(V, dtype=torch.float32, device="cuda")
+        target.spd_prefill(s, torch.from_numpy(x.astype(np.float32)).cuda(), last)
+        draft.spd_prefill_tokens(s, torch.from_numpy(toks).cuda())
+        check_logits(last.cpu().numpy(), ref_last, f"prefill seq {s}")
+        t = ss.sample_row(ss.softmax_probs(last.cpu().numpy(), temperature), u_first[s])
+        # loop convention: the draft's cache ends before the token that precedes t
+        d_cache.truncate(n_text - 1)
+        oracle.append(dict(t_cache=t_cache, d_cache=d_cache, prev=int(toks[-1]), t=t, out=[]))
+        loop.vt[s, 0] = t
+        loop.din[s, 0] = int(toks[-1])
+        loop.din[s, 1] = t
+    draft.spd_kv_set_len([o["d_cache"].length for o in oracle])
+    target.spd_kv_lens_to_device()
+    draft.spd_kv_lens_to_device()
+    return loop, oracle, (tc, twn, dc, dwn)
+
+
+def check_block_against_oracle(loop, oracle, models, u_draft_b, u_accept_b, b):
+    tc, twn, dc, dwn = models
+    g, temperature = loop.gamma, loop.temperature
+    D_all, lg_all = loop.D.cpu().numpy(), loop.logits.cpu().numpy()
+    k_all, y_all = loop.k.cpu().numpy(), loop.y.cpu().numpy()
+    ks = []
+    for s, o in enumerate(oracle):
+        pending, d_tokens = [o["prev"], o["t"]], []
+        for j in range(g):
+            ref = dec.forward_tokens(dc, dwn, o["d_cache"], pending)[-1]
+            D_ref = ss.softmax_probs(ref, temperature)
+            D_j = D_all[s, j]
+            big = D_ref > 1e-12
+            assert np.max(np.abs(np.log(D_j[big].astype(np.float64)) - np.log(D_ref[big].astype(np.float64)))) < 2 * 3e-2 / temperature
+            d_j = ss.sample_row(D_j, u_draft_b[s, j])          # the device must have drawn exactly this token
+            d_tokens.append(d_j)
+            pending = [d_j]
+        P = o["t_cache"].length
+        ref_t = dec.forward_tokens(tc, twn, o["t_cache"], [o["t"]] + d_tokens)
+        check_logits(lg_all[s], ref_t, f"block {b} seq {s}")
+        # the product decides on its own float32 softmax of the logits; the oracle's float64 softmax of the
+        # same logits may differ at near-ties only
+        T_rows = ss.softmax_probs(lg_all[s], temperature)
+        k_ref, y_ref = ss.speculative_accept(T_rows, D_all[s], d_tokens, u_accept_b[s])
+        k, y = int(k_all[s]), int(y_all[s])
+        margins = [abs(float(u_accept_b[s, j]) * float(D_all[s, j, d_tokens[j]]) - float(T_rows[j, d_tokens[j]])) /
+                   max(float(T_rows[j, d_tokens[j]]), 1e-30) for j in range(g)]
+        if min(margins) > 1e-3:
+            assert k == k_ref, (b, s, k, k_ref)
+        emitted = d_tokens[:k] + [y]
+        o["out"].extend(emitted)
+        o["t_cache"].truncate(P + k + 1)
+        o["d_cache"].truncate(o["d_cache"].length - (g - k))
+        o["prev"] = d_tokens[k - 1] if k >= 1 else o["t"]
+        o["t"] = y
+        ks.append(k)
+    return ks
+
+
+@pytest.mark.parametrize("n_seqs,gamma", [(1, 4), (3, 3)])
+def test_device_block_loop_lockstep(n_seqs, gamma):
+    """No host decision between blocks: lengths, tokens and the commit stay on the device."""
+    n_blocks, temperature, seed = 6, 1.0, 31
+    loop, oracle, models = setup_device_loop(n_seqs, gamma, n_blocks, temperature, seed, m_img=16)
+    u_draft = synth.uniforms((n_blocks, n_seqs, gamma), seed + 2)
+    u_accept = synth.uniforms((n_blocks, n_seqs, gamma + 1), seed + 3)
+    all_ks = []
+    for b in range(n_blocks):
+        print(f"device loop block {b}", flush=True)
+        loop.u_draft.copy_(torch.from_numpy(u_draft[b]))
+        loop.u_accept.copy_(torch.from_numpy(u_accept[b]))
+        loop.block()
+        all_ks.append(check_block_against_oracle(loop, oracle, models, u_draft[b], u_accept[b], b))
+    print("accepted per block", all_ks)
+    loop.target.spd_kv_lens_from_device()
+    loop.draft.spd_kv_lens_from_device()
+    assert loop.target.spd_kv_get_len(n_seqs) == [o["t_cache"].length for o in oracle]
+    assert loop.draft.spd_kv_get_len(n_seqs) == [o["d_cache"].length for o in oracle]
+    n_out = loop.n_out.cpu().numpy()
+    out = loop.out.cpu().numpy()
+    for s, o in enumerate(oracle):
+        assert n_out[s] == len(o["out"]) and list(out[s, :n_out[s]]) == o["out"]
+    loop.target.close()
+    loop.draft.close()
+
+
+def test_device_block_loop_as_graph_replays_equal_eager():
+    """One block captured in a graph and replayed: every replay (with eager copies of the next
+    uniforms and host synchronisation in between) gives what the eager launches give."""
+    n_seqs, gamma, n_blocks, temperature, seed = 2, 4, 5, 1.0, 37
+    u_draft = synth.uniforms((n_blocks, n_seqs, gamma), seed + 2)
+    u_accept = synth.uniforms((n_blocks, n_seqs, gamma + 1), seed + 3)
+    results = {}
+    for mode in ("eager", "graph"):
+        loop, oracle, _ = setup_device_loop(n_seqs, gamma, n_blocks + 2, temperature, seed, m_img=8)
+        graph = None
+        if mode == "graph":
+            # warm-up launches on a side stream (as the capture API asks), then restore the state they changed
+            saved = [t.clone() for t in (loop.vt, loop.din, loop.out, loop.n_out)]
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(s):
+                loop.block()
+            torch.cuda.current_stream().wait_stream(s)
+            torch.cuda.synchronize()
+            loop.target.spd_kv_lens_from_device()
+            loop.draft.spd_kv_lens_from_device()
+            loop.target.spd_kv_set_len([o["t_cache"].length for o in oracle])
+            loop.draft.spd_kv_set_len([o["d_cache"].length for o in oracle])
+            loop.target.spd_kv_lens_to_device()
+            loop.draft.spd_kv_lens_to_device()
+            for t, sv in zip((loop.vt, loop.din, loop.out, loop.n_out), saved):
+                t.copy_(sv)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                loop.block()
+            # capture runs nothing: state is still the restored one
+        ks, ys = [], []
+        for b in range(n_blocks):
+            loop.u_draft.copy_(torch.from_numpy(u_draft[b]))
+            loop.u_accept.copy_(torch.from_numpy(u_accept[b]))
+            if graph is None:
+                loop.block()
+            else:
+                graph.replay()
+            torch.cuda.synchronize()
+            ks.append(loop.k.cpu().numpy().copy())
+            ys.append(loop.y.cpu().numpy().copy())
+        loop.target.spd_kv_lens_from_device()
+        loop.draft.spd_kv_lens_from_device()
+        results[mode] = (np.stack(ks), np.stack(ys), loop.out.cpu().numpy().copy(), loop.n_out.cpu().numpy().copy(),
+                         loop.target.spd_kv_get_len(n_seqs), loop.draft.spd_kv_get_len(n_seqs), loop.logits.cpu().numpy().copy())
+        loop.target.close()
+        loop.draft.close()
+    for a, b in zip(results["eager"], results["graph"]):
+        assert np.array_equal(np.asarray(a), np.asarray(b))
+    assert results["eager"][3].min() >= n_blocks
