@@ -234,6 +234,13 @@ int32_t spd_block_finish(spd_model *target, spd_model *draft, const float *targe
                          int32_t *out_tokens, int32_t out_capacity, int32_t *n_out,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* Waits for `stream` and reports conditions that kernels can only flag on the device:
+ * SPD_ERR_HIP if a bounded wait between workgroups (fused QKV + attention kernel, whole-forward
+ * kernel) ever ran into its spin limit -- never in a healthy run; results since then are
+ * invalid --, SPD_ERR_CAPACITY if a forward in device-length mode found no room for its rows,
+ * else SPD_OK. */
+int32_t spd_device_status(spd_model *model, void *stream);
+
 /* Tracing aid (not part of the method).  While enabled, every kernel launch group of
  * this model's forward passes is bracketed by a pair of HIP events on the caller's
  * stream (host-side event objects only: no device memory).  spd_trace_read WAITS for

@@ -83,6 +83,27 @@ struct AttnArgs {
 };
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream);
 
+// ---- QKV projection and attention in one kernel (one row group, one sequence, K = 4096, head_dim 128) ----
+// One workgroup per (head, 16 output dimensions) computes the three 16-row tiles of the fused
+// QKV matrix that hold its slice of q, k and v, announces them on the head's arrival counter,
+// and -- once all slices of the head have arrived -- runs attention for its slice.  The
+// dependency between the two stages is per head, so no device-wide barrier is needed; the
+// loads of the cached keys and values are in flight while the counter is awaited.
+struct QkvAttnArgs {
+    const void *W;            // packed [3 * H * dh, K]
+    const void *X;            // packed activations, one row group
+    int K, rows;
+    const float *ssq_in;      // as in GemmArgs
+    int ssq_in_parts;
+    float eps;
+    AttnArgs at;              // at.qkv: float32 [rows][3 * H * dh] scratch filled by the projection part
+    unsigned *head_count;     // [H] arrival counters; every launch adds dh / 16 to each
+    unsigned count_before;    // their common value before this launch
+    int *abort_flag;          // raised (and never cleared) if a wait hit its spin limit
+};
+bool qkv_attention_supported(int K, int H, int dh, int rows, int n_seqs, int M);
+hipError_t launch_qkv_attention(const QkvAttnArgs &a, hipStream_t stream);
+
 // ---- whole forward in one persistent kernel (rows <= 5) -------------------------------------
 struct MegaArgs {
     // model

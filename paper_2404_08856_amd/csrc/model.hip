@@ -49,7 +49,7 @@ struct Layout {                    // byte offsets inside the three buffers
     size_t kv_layer_stride, kv_k_bytes, kv_v_bytes, kv_total;
     int v_stride;
     // workspace
-    size_t h, qkv, xn, xo, xf, rope, logits, ssq_a, ssq_b, d_lens, d_error, ws_total;
+    size_t h, qkv, xn, xo, xf, rope, logits, ssq_a, ssq_b, d_lens, d_error, qa_count, qa_abort, ws_total;
     size_t m_hg, m_att, m_xf, m_ssq_a, m_ssq_b, m_sync, m_clock;     // arrays of the whole-forward kernel (8 rows)
 };
 
@@ -103,6 +103,8 @@ void make_layout(const spd_model_config &c, Layout &L) {
     L.logits = take((size_t)kMaxRows * V * 4);
     L.d_lens = take((size_t)kMaxRows * 4);
     L.d_error = take(4);
+    L.qa_count = take((size_t)c.n_heads * 4);
+    L.qa_abort = take(4);
     L.ssq_a = take((size_t)(d / 16) * kMaxRows * 4);
     L.ssq_b = take((size_t)(d / 16) * kMaxRows * 4);
     L.m_hg = take((size_t)8 * d * 4);
@@ -160,6 +162,8 @@ struct spd_model {
     char *packed, *kv, *ws;
     std::vector<int32_t> lens;         // KV lengths (host).  With dev_lens: only an upper bound
     bool dev_lens = false;             // the kernels read the lengths from device memory (ws + L.d_lens)
+    bool fuse_qa = false;              // QKV projection + attention as one kernel where the shape allows it
+    unsigned qa_count = 0;             // value of that kernel's per-head arrival counters after the last launch
     std::vector<float> rope_host;
     GemmTuning t_qkv, t_o, t_gu, t_down, t_lm;
     int mega_grid = 0;                 // workgroups of the whole-forward kernel (0: not available)
@@ -294,6 +298,8 @@ int32_t spd_model_create(const spd_model_config *cfg, const spd_weights *w, void
     // Whole-forward persistent kernel for calls of up to 8 rows.  Opt-in (SPD_MEGA=1): at the 7B
     // shape its device-wide barriers and lock-step stages currently cost more than the launch
     // gaps of the per-stage kernels they remove, so the per-stage path is the default.
+    // fused QKV + attention (SPD_NO_FUSE=1 keeps the two kernels)
+    m->fuse_qa = !getenv("SPD_NO_FUSE") && qkv_attention_supported(cfg->d_model, cfg->n_heads, cfg->head_dim, 1, 1, 1);
     m->mega_grid = 0;
     if (getenv("SPD_MEGA") && cfg->n_layers > 0) m->mega_grid = megakernel_max_grid(cfg->head_dim);
     if (const char *e = getenv("SPD_MEGA_GRID")) { int g = atoi(e); if (g > 0 && g < m->mega_grid) m->mega_grid = g; }
@@ -338,6 +344,18 @@ int32_t spd_kv_lens_from_device(spd_model *m, void *stream) {
     const bool overflow = tmp[m->cfg.max_seqs] != 0;
     for (int i = 0; i < m->cfg.max_seqs; ++i) m->lens[i] = std::max(0, std::min(tmp[i], m->cfg.max_positions));
     if (overflow) return fail(SPD_ERR_CAPACITY, "a forward ran with a device KV length that left no room for its rows");
+    return SPD_OK;
+}
+
+int32_t spd_device_status(spd_model *m, void *stream) {
+    if (!m) return fail(SPD_ERR_INVALID_ARG, "NULL model");
+    int32_t flags[3] = {0, 0, 0};
+    HIP_TRY(hipMemcpyAsync(&flags[0], m->ws + m->L.d_error, 4, hipMemcpyDeviceToHost, (hipStream_t)stream));
+    HIP_TRY(hipMemcpyAsync(&flags[1], m->ws + m->L.qa_abort, 4, hipMemcpyDeviceToHost, (hipStream_t)stream));
+    HIP_TRY(hipMemcpyAsync(&flags[2], m->ws + m->L.m_sync + 64, 4, hipMemcpyDeviceToHost, (hipStream_t)stream));
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    if (flags[1] || flags[2]) return fail(SPD_ERR_HIP, "a wait between workgroups hit its spin limit: results since then are invalid");
+    if (flags[0]) return fail(SPD_ERR_CAPACITY, "a forward ran with a device KV length that left no room for its rows");
     return SPD_OK;
 }
 
@@ -420,20 +438,33 @@ int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const flo
     at.n_seqs = n_seqs; at.M = M; at.H = c.n_heads; at.dh = c.head_dim; at.max_positions = c.max_positions;
     at.v_stride = L.v_stride;
 
+    const bool fused = m->fuse_qa && rows <= kGroupRows && n_seqs == 1;   // the shape was checked at creation
     for (int l = 0; l < c.n_layers; ++l) {
         // RMSNorm is folded into the projections: the producer of h (input rows / O / down
         // epilogue) leaves packed (h * gain) and per-tile sums of squares; the consumer
         // scales its accumulators by 1 / rms.
-        GemmArgs g{};
-        g.W = m->packed + L.wqkv[l]; g.X = xn; g.N = 3 * HD; g.K = d; g.rows = rows; g.Y = qkv; g.ldy = 3 * HD;
-        g.ssq_in = ssq_b; g.ssq_in_parts = (l == 0) ? 1 : d_tiles; g.eps = c.rms_eps;
-        PROF_TRY(PK_QKV, launch_gemm(g, EPI_STORE, m->t_qkv, st));
         char *kv_l = m->kv + (size_t)l * L.kv_layer_stride;
         at.k_cache = kv_l + (size_t)seq0 * c.n_heads * c.max_positions * c.head_dim * 2;
         at.v_cache = kv_l + align_up(L.kv_k_bytes, 256) + (size_t)seq0 * c.n_heads * c.head_dim * L.v_stride * 2;
-        for (int m0 = 0; m0 < M; m0 += kGroupRows) {         // at most 5 queries per sequence and launch
-            at.m0 = m0; at.Mq = std::min(kGroupRows, M - m0);
-            PROF_TRY(PK_ATTENTION, launch_attention(at, st));
+        GemmArgs g{};
+        if (fused) {
+            QkvAttnArgs qa{};
+            qa.W = m->packed + L.wqkv[l]; qa.X = xn; qa.K = d; qa.rows = rows;
+            qa.ssq_in = ssq_b; qa.ssq_in_parts = (l == 0) ? 1 : d_tiles; qa.eps = c.rms_eps;
+            at.m0 = 0; at.Mq = M;
+            qa.at = at;
+            qa.head_count = (unsigned *)(m->ws + L.qa_count); qa.count_before = m->qa_count;
+            qa.abort_flag = (int *)(m->ws + L.qa_abort);
+            PROF_TRY(PK_QKV, launch_qkv_attention(qa, st));
+            m->qa_count += (unsigned)(c.head_dim / 16);
+        } else {
+            g.W = m->packed + L.wqkv[l]; g.X = xn; g.N = 3 * HD; g.K = d; g.rows = rows; g.Y = qkv; g.ldy = 3 * HD;
+            g.ssq_in = ssq_b; g.ssq_in_parts = (l == 0) ? 1 : d_tiles; g.eps = c.rms_eps;
+            PROF_TRY(PK_QKV, launch_gemm(g, EPI_STORE, m->t_qkv, st));
+            for (int m0 = 0; m0 < M; m0 += kGroupRows) {         // at most 5 queries per sequence and launch
+                at.m0 = m0; at.Mq = std::min(kGroupRows, M - m0);
+                PROF_TRY(PK_ATTENTION, launch_attention(at, st));
+            }
         }
         g = GemmArgs{};
         g.W = m->packed + L.wo[l]; g.X = xo; g.N = d; g.K = HD; g.rows = rows; g.Y = h; g.ldy = d;

@@ -26,7 +26,7 @@ EXPORTS = ["spd_last_error", "spd_model_bytes", "spd_model_create", "spd_model_d
            "spd_kv_get_len", "spd_prefill", "spd_prefill_tokens", "spd_verify_forward", "spd_draft_step",
            "spd_accept_workspace_bytes", "spd_speculative_accept", "spd_trace_enable", "spd_trace_read",
            "spd_trace_stages", "spd_kv_lens_to_device", "spd_kv_lens_from_device", "spd_draft_step_strided",
-           "spd_block_finish"]
+           "spd_block_finish", "spd_device_status"]
 TRACE_KINDS = ["qkv", "o", "gate_up", "down", "lm_head", "attention", "forward", "embed"]
 
 
@@ -74,6 +74,7 @@ _lib.spd_trace_read.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_double), ctyp
 _lib.spd_trace_stages.argtypes = [_vp, _i32] + [ctypes.POINTER(ctypes.c_double)] * 4 + [ctypes.POINTER(_i32)]
 _lib.spd_kv_lens_to_device.argtypes = [_vp, _vp]
 _lib.spd_kv_lens_from_device.argtypes = [_vp, _vp]
+_lib.spd_device_status.argtypes = [_vp, _vp]
 _lib.spd_draft_step_strided.argtypes = [_vp, _vp, _i32, _i32, _i32, _f32, _vp, _i32, _vp, _sz, _vp, _i32, _vp]
 _lib.spd_block_finish.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
 for _name in EXPORTS:
@@ -200,6 +201,9 @@ class Model:
                                            float(temperature), _raw(u_draft, torch.float32), u_stride,
                                            _raw(D_row_out, torch.float32), D_stride, _raw(token_out, torch.int32),
                                            token_stride, _stream()))
+
+    def spd_device_status(self):
+        _check(_lib.spd_device_status(self.handle, _stream()))
 
     def spd_kv_lens_to_device(self):
         _check(_lib.spd_kv_lens_to_device(self.handle, _stream()))

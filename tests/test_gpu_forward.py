@@ -295,3 +295,32 @@ def test_batched_verify_many_row_groups(n_seqs, M):
         check_logits(got[s], dec.forward_tokens(cfg, wn, caches[s], vt[s]), f"seq {s}")
     assert model.spd_kv_get_len(n_seqs) == [c.length for c in caches]
     model.close()
+
+
+@pytest.mark.parametrize("fuse", [True, False])
+@pytest.mark.parametrize("M", [1, 5])
+def test_qkv_attention_fused_and_separate_kernels(fuse, M, monkeypatch):
+    """d_model 4096 with 2 heads of 128: the shape class that takes the fused QKV + attention kernel
+    (one workgroup per head and 16 output dimensions, per-head arrival counter), against the
+    oracle, with the fusion on and off; several calls so that the counters advance."""
+    if not fuse:
+        monkeypatch.setenv("SPD_NO_FUSE", "1")
+    shape = synth.ModelShape(2, 4096, 2, 128, 256, 1024)
+    print(f"case fused={fuse} M={M}", flush=True)
+    spd = spd_mod()
+    model, wn = build_pair(shape, 51, 1, 128)
+    cfg = oracle_cfg(shape)
+    cache = dec.KVCache(cfg, 128)
+    toks = synth.text_tokens(70, shape.vocab, 51)
+    ref_last = dec.forward_tokens(cfg, wn, cache, toks)[-1]
+    last = torch.empty(shape.vocab, dtype=torch.float32, device="cuda")
+    model.spd_prefill_tokens(0, torch.from_numpy(toks).cuda(), last)
+    check_logits(last.cpu().numpy(), ref_last, "prefill")
+    for step in range(3):
+        vt = synth.text_tokens(M, shape.vocab, 60 + step)
+        ref = dec.forward_tokens(cfg, wn, cache, vt)
+        out = torch.empty((1, M, shape.vocab), dtype=torch.float32, device="cuda")
+        model.spd_verify_forward(torch.from_numpy(vt).cuda()[None].contiguous(), out)
+        check_logits(out.cpu().numpy()[0], ref, f"step {step}")
+    model.spd_device_status()
+    model.close()
