@@ -324,3 +324,83 @@ def test_qkv_attention_fused_and_separate_kernels(fuse, M, monkeypatch):
         check_logits(out.cpu().numpy()[0], ref, f"step {step}")
     model.spd_device_status()
     model.close()
+
+
+def test_sixty_four_sequences_of_one_row():
+    """The row limit with one row per sequence: 64 sequences, 13 row groups, every sequence its own length."""
+    shape = synth.SHAPES["tiny_draft"]
+    n_seqs = 64
+    model, wn = build_pair(shape, 19, n_seqs, 24)
+    cfg = oracle_cfg(shape)
+    caches, toks_in = [], []
+    for s in range(n_seqs):
+        n = 1 + s % 11
+        toks = synth.text_tokens(n, shape.vocab, 300 + s)
+        c = dec.KVCache(cfg, 24)
+        dec.forward_tokens(cfg, wn, c, toks)
+        caches.append(c)
+        model.spd_prefill_tokens(s, torch.from_numpy(toks).cuda())
+    vt = synth.text_tokens(n_seqs, shape.vocab, 400).reshape(n_seqs, 1)
+    out = torch.empty((n_seqs, 1, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_verify_forward(torch.from_numpy(vt).cuda(), out)
+    got = out.cpu().numpy()
+    for s in range(n_seqs):
+        check_logits(got[s], dec.forward_tokens(cfg, wn, caches[s], vt[s]), f"seq {s}")
+    model.close()
+
+
+def test_device_length_overflow_is_flagged_not_faulted():
+    """Device-resident KV lengths cannot be checked by the host before a launch.  A forward that
+    finds no room for its rows must stay inside the cache (it works on a clamped length) and
+    raise the flag that spd_kv_lens_from_device reports."""
+    spd = spd_mod()
+    shape = synth.SHAPES["tiny_draft"]
+    model, _ = build_pair(shape, 23, 1, 16)
+    model.spd_prefill_tokens(0, torch.from_numpy(synth.text_tokens(10, shape.vocab, 1)).cuda())
+    model.spd_kv_lens_to_device()
+    out = torch.empty((1, 5, shape.vocab), dtype=torch.float32, device="cuda")
+    vt = torch.from_numpy(synth.text_tokens(5, shape.vocab, 2)).cuda()[None].contiguous()
+    model.spd_verify_forward(vt, out)           # 10 + 5 <= 16: fine
+    model.spd_device_status()
+    model.spd_verify_forward(vt, out)           # 15 + 5 > 16: flagged
+    torch.cuda.synchronize()
+    with pytest.raises(spd.SpdError) as e:
+        model.spd_device_status()
+    assert e.value.code == spd.SPD_ERR_CAPACITY
+    with pytest.raises(spd.SpdError) as e:
+        model.spd_kv_lens_from_device()
+    assert e.value.code == spd.SPD_ERR_CAPACITY
+    assert model.spd_kv_get_len(1)[0] <= 16
+    with pytest.raises(spd.SpdError):           # lengths are back on the host: the usual refusal applies
+        model.spd_kv_set_len([17])
+    model.close()
+
+
+def test_image_aware_draft_takes_embedding_rows():
+    """A draft that also sees the image (the fine-tuned variant with its own projector output,
+    Section 3 / Table 1): its prefill takes [image rows of the draft's width ; text embeddings]
+    exactly like the target's; draft steps then run at positions after the image rows."""
+    shape = synth.SHAPES["tiny_draft"]
+    model, wn = build_pair(shape, 29, 1, 64)
+    cfg = oracle_cfg(shape)
+    toks = synth.text_tokens(9, shape.vocab, 29)
+    x = np.concatenate([synth.image_rows(12, shape.d_model, 29).astype(np.float64), dec.embed_tokens(wn, toks)])
+    cache = dec.KVCache(cfg, 64)
+    ref_last = dec.forward_rows(cfg, wn, cache, x)[-1]
+    last = torch.empty(shape.vocab, dtype=torch.float32, device="cuda")
+    model.spd_prefill(0, torch.from_numpy(x.astype(np.float32)).cuda(), last)
+    check_logits(last.cpu().numpy(), ref_last, "image-aware draft prefill")
+    from oracle import spec_sampling as ss
+    D = torch.empty((1, shape.vocab), dtype=torch.float32, device="cuda")
+    tok = torch.empty((1,), dtype=torch.int32, device="cuda")
+    u = synth.uniforms((3,), 30)
+    t = 7
+    for j in range(3):
+        ref = dec.forward_tokens(cfg, wn, cache, [t])[0]
+        model.spd_draft_step(torch.tensor([[t]], dtype=torch.int32, device="cuda"), 1.0, torch.from_numpy(u[j:j + 1]).cuda(), D, tok)
+        D_gpu, D_ref = D.cpu().numpy()[0], ss.softmax_probs(ref, 1.0)
+        assert np.max(np.abs(np.log(D_gpu.astype(np.float64)) - np.log(D_ref.astype(np.float64)))) < 2 * 3e-2
+        assert int(tok.item()) == ss.sample_row(D_gpu, u[j])
+        t = int(tok.item())
+    assert model.spd_kv_get_len(1) == [12 + 9 + 3]
+    model.close()
