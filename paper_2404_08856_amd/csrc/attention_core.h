@@ -3,7 +3,7 @@
 // with 6..8 rows per sequence takes two launches: the second sees the first one's rows in the
 // cache like any other prefix position.
 //
-// One workgroup (12 waves) per (sequence, head, 16 output dimensions).  The cached keys are cut
+// One workgroup (12 waves) per (sequence, head, slice of 16 or more output dimensions).  The cached keys are cut
 // into units of 32; every wave owns a contiguous run of units and walks it 2 units (64 keys)
 // at a time.  All loads of an iteration -- the K rows and the V columns of the wave's keys --
 // are issued before anything is computed, so for contexts up to 768 keys the whole kernel pays
@@ -24,9 +24,9 @@
 // second product: no data moves between lanes.
 //
 // The M new keys/values (this call's own rows, causal among themselves) are handled from
-// LDS with plain float32 arithmetic as one more partial; the 8 + 1 partials are merged in a
-// fixed order.  K (after RoPE) and V are rounded to bf16 -- the cache precision -- before
-// they are used, appended to the cache, and the result is written as bf16 head + tail in
+// LDS with plain float32 arithmetic as one more partial; the partials (one per wave + this one)
+// are merged in a fixed order.  K (after RoPE) and V are rounded to bf16 -- the cache precision -- before
+// they are used, appended to the cache, and the result is written as three bf16 terms in
 // B-operand order for the O projection.
 #pragma once
 #include "launch.h"
@@ -88,7 +88,7 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
     __shared__ float qf[8][DH];
     __shared__ float kf[8][DH];
     __shared__ float vf[8][DH];
-    __shared__ uint16_t qb[NC][64][8];            // q as matrix-core B operand (head | tail)
+    __shared__ uint16_t qb[NC][64][8];            // q as matrix-core B operand (three bf16 terms)
     __shared__ float pn[8][8];
     __shared__ float part_m[AW + 1][8];
     __shared__ float part_l[AW + 1][8];
@@ -252,7 +252,7 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
     if (lane < kGroupRows) { part_m[w][lane] = m_run; part_l[w][lane] = l_run; }
 
     // ---- the M new keys (causal among the new rows), float32 from LDS -----------------------
-    if (w == AW - 1) {
+    if (w == 0) {                                   // wave 0 owns the fewest key units
         const int m = lane >> 3, j = lane & 7;
         float s = -INFINITY;
         if (m < M && j <= m) {
@@ -272,7 +272,7 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
         if (j == 0) { part_m[AW][m] = mx; part_l[AW][m] = l; }
     }
     __syncthreads();
-    if (w == AW - 1) {
+    if (w == 0) {                                   // wave 0 owns the fewest key units
         const int m = lane >> 3, j = lane & 7;
         for (int dd = j; dd < DW; dd += 8) {
             float o = 0.f;

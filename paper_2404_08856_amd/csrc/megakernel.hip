@@ -79,7 +79,7 @@ __device__ __forceinline__ void grid_barrier(unsigned *bar, unsigned target, int
 // ---- B operand from a float32 activation array --------------------------------------------
 // One K-step of the B operand is 8 rows x 32 floats = one 16-byte load per lane: lane l reads
 // row l / 8, floats 4 (l % 8) .. +3.  conv = 1 KiB of LDS private to the wave, used to
-// re-arrange the head/tail halves into operand order (lane c + 16 g: column c, k = 8 g .. 8 g + 7).
+// re-arrange the three bf16 terms into operand order (lane c + 16 g: column c, k = 8 g .. 8 g + 7).
 __device__ __forceinline__ uint4 to_b_operand(fx4 raw, bool row_valid, uint2 *conv, int lane) {
     const int rho = lane >> 3, kap = lane & 7;
     union { uint2 v; uint16_t h[4]; } term[kTerms];
