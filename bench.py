@@ -167,6 +167,7 @@ def side_configs(args, spd, synth, torch):
         abytes = n_seqs * (2 * args.gamma + 1) * V * 4
         per_sigma[str(sigma)] = {"us": us, "GBps": abytes / (us * 1e-6) / 1e9, "mean_accepted": float(k.float().mean())}
     res["block_loop"] = block_loop(args, spd, synth, torch)
+    res["batched_verify"] = batched_verify(args, spd, synth, torch)
     res["accept_kernel"] = {"workload": f"{n_seqs} sequences x (gamma+1={args.gamma + 1}) rows x vocab {V}, logit inputs, temperature 1; "
                                         "draft logits = target + N(0, sigma^2)",
                             "algorithmic_bytes": n_seqs * (2 * args.gamma + 1) * V * 4, "by_sigma": per_sigma,
@@ -275,6 +276,42 @@ def block_loop(args, spd, synth, torch):
                 "(results figure: block efficiency above 2 at draft lengths 3 and 5, memory-bound speed-up up to 2.37)"}
     target.close()
     draft.close()
+    return res
+
+
+def batched_verify(args, spd, synth, torch):
+    """The 7B verify step for several sequences at once (rows = sequences x (gamma + 1) span several row groups)."""
+    M = args.gamma + 1
+    ts = synth.SHAPES["llama7b"]
+    n_prefix = args.image_rows + args.text_tokens
+    n_max = 8
+    model = spd.Model(spd.make_config(ts, n_max, n_prefix + M + 3), synth.make_weights(ts, args.seed, device="cuda"))
+    torch.cuda.empty_cache()
+    # one real prefill; the other sequences reuse its length over a zero-filled cache (timing only)
+    model.spd_prefill(0, torch.from_numpy(synth.image_rows(args.image_rows, ts.d_model, args.seed)).cuda())
+    model.spd_prefill_tokens(0, torch.from_numpy(synth.text_tokens(args.text_tokens, ts.vocab, args.seed)).cuda())
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    res = {"workload": f"7B target, prefix {n_prefix} per sequence, gamma+1={M} tokens per sequence, forward only"}
+    for B in (2, 4, 8):
+        vt = torch.from_numpy(synth.text_tokens(B * M, ts.vocab, args.seed + 30).reshape(B, M)).cuda()
+        out = torch.empty((B, M, ts.vocab), dtype=torch.float32, device="cuda")
+
+        def step():
+            model.spd_kv_set_len([n_prefix] * B)
+            model.spd_verify_forward(vt, out)
+
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        reps = 20
+        e0.record()
+        for _ in range(reps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        res[f"batch_{B}"] = {"ms_per_step": ms, "verified_tokens_per_s": B * M / (ms * 1e-3)}
+    model.close()
     return res
 
 

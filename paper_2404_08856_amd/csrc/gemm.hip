@@ -253,6 +253,143 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs 
     }
 }
 
+// More than one row group (6..64 rows): NG groups and TT weight tiles are in flight together.
+// A weight block is used by all NG groups (NG matrix-core steps), an activation block by all
+// TT tiles, so per streamed weight byte the workgroup reads (TT + NG) / TT bytes through its
+// L1 instead of 1 + NG.  (Reading the activation blocks anew for every single tile, as the
+// kernel above does, was measured at 2-3x the one-group time already for 2 groups: every
+// workgroup of the chip asks the same L2 lines at the same moment.)  Persistent workgroups own
+// groups of TT consecutive tiles (the last group may be ragged); 8 waves split K; two K-steps
+// of loads are in flight per wave while the previous step is multiplied.
+template <int NG, int TT, int EPI>
+__global__ __launch_bounds__(512) void gemm_multi_kernel(GemmKernelArgs a) {
+    constexpr int WAVES = 8;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int KS = a.KS;
+    const int s0 = (int)(((long)KS * w) / WAVES), s1 = (int)(((long)KS * (w + 1)) / WAVES);
+    const int g0 = a.row0 / kGroupRows;
+    const int n_groups_t = (a.n_tiles + TT - 1) / TT;     // tile groups
+    const int ngv = (a.rows + kGroupRows - 1) / kGroupRows;   // row groups that hold rows of this pass (<= NG)
+
+    __shared__ float red[WAVES][TT][NG][16][8];
+    __shared__ float inv_s[kMaxRows];
+
+    if (a.ssq_in) {
+        for (int r = a.row0 + w; r < a.row0 + a.rows; r += WAVES) {
+            float sum = 0.f;
+            for (int p = lane; p < a.ssq_in_parts; p += 64) sum += a.ssq_in[(size_t)r * (KS * 2) + p];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+            if (lane == 0) inv_s[r] = 1.0f / sqrtf(sum * a.inv_d + a.eps);
+        }
+    } else if (threadIdx.x < kMaxRows) {
+        inv_s[threadIdx.x] = 1.0f;
+    }
+    __syncthreads();
+
+    for (int tg = blockIdx.x; tg < n_groups_t; tg += gridDim.x) {
+        const int t0 = tg * TT;
+        uint4 av[2][TT], bv[2][NG];
+        auto load_step = [&](int buf, int s) {            // blocks of K-step s (tiles beyond the matrix: tile 0, unused)
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                const int t = t0 + tt < a.n_tiles ? t0 + tt : 0;
+                av[buf][tt] = load_stream(a.W + ((size_t)t * KS + s) * 64 + lane);
+            }
+#pragma unroll
+            for (int g = 0; g < NG; ++g)                  // groups beyond this pass's rows: re-read the first one, result unused
+                bv[buf][g] = a.X[((size_t)(g0 + (g < ngv ? g : 0)) * KS + s) * 64 + lane];
+        };
+        f32x4_t acc[TT][NG];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[tt][g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (s0 < s1) load_step(0, s0);
+        if (s0 + 1 < s1) load_step(1, s0 + 1);
+        for (int s = s0; s < s1; s += 2) {
+#pragma unroll
+            for (int buf = 0; buf < 2; ++buf) {
+                if (s + buf < s1) {                       // wave-uniform
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                        for (int g = 0; g < NG; ++g) acc[tt][g] = mfma_bf16(av[buf][tt], bv[buf][g], acc[tt][g]);
+                    if (s + buf + 2 < s1) load_step(buf, s + buf + 2);
+                }
+            }
+        }
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float x = sum_terms(acc[tt][g][v]);
+                    if ((lane & 15) < kGroupRows) red[w][tt][g][4 * (lane >> 4) + v][lane & 15] = x;
+                }
+        __syncthreads();
+        // epilogue: one element (tile tt, group g, row slot em, column en) per thread and round
+        for (int e = threadIdx.x; e < TT * NG * 128; e += WAVES * 64) {
+            const int en = e & 15, em = (e >> 4) & 7, g = (e >> 7) % NG, tt = (e >> 7) / NG;
+            const int t = t0 + tt;
+            const int erow = a.row0 + g * kGroupRows + em;
+            const bool ok = em < kGroupRows && erow < a.row0 + a.rows && t < a.n_tiles;
+            if (EPI == EPI_SWIGLU) {
+                if (ok && en < 8) {
+                    float gate = 0.f, up = 0.f;
+#pragma unroll
+                    for (int ww = 0; ww < WAVES; ++ww) { gate += red[ww][tt][g][en][em]; up += red[ww][tt][g][en + 8][em]; }
+                    gate *= inv_s[erow];
+                    up *= inv_s[erow];
+                    uint16_t t3[kTerms];
+                    split3(gate / (1.0f + expf(-gate)) * up, t3);
+#pragma unroll
+                    for (int q = 0; q < kTerms; ++q) a.Xout[xpack_index(erow, t * 8 + en, a.KS_out, q)] = t3[q];
+                }
+            } else {
+                float sum = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ++ww) sum += red[ww][tt][g][en][em];
+                const int col = t * 16 + en;
+                if (EPI == EPI_STORE) {
+                    if (ok) a.Y[(size_t)erow * a.ldy + col] = sum * inv_s[erow];
+                } else {
+                    float hnew = 0.f;
+                    if (ok) {
+                        hnew = a.Y[(size_t)erow * a.ldy + col] + sum;
+                        a.Y[(size_t)erow * a.ldy + col] = hnew;
+                        if (a.gain_next) {
+                            uint16_t t3[kTerms];
+                            split3(hnew * a.gain_next[col], t3);
+#pragma unroll
+                            for (int q = 0; q < kTerms; ++q) a.Xnext[xpack_index(erow, col, a.n_tiles / 2, q)] = t3[q];
+                        }
+                    }
+                    float sq = hnew * hnew;                // the 16 columns of a row slot sit in 16 neighbouring lanes
+#pragma unroll
+                    for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
+                    if (a.ssq_out && en == 0 && ok) a.ssq_out[(size_t)erow * a.n_tiles + t] = sq;
+                }
+            }
+        }
+        __syncthreads();                                  // `red` is rewritten by the next tile group
+    }
+}
+
+template <int NG, int TT>
+static hipError_t launch_multi(const GemmKernelArgs &k, int epilogue, int grid, hipStream_t stream) {
+    dim3 g(grid), block(512);
+    switch (epilogue) {
+        case EPI_STORE: hipLaunchKernelGGL((gemm_multi_kernel<NG, TT, EPI_STORE>), g, block, 0, stream, k); break;
+        case EPI_RESIDUAL: hipLaunchKernelGGL((gemm_multi_kernel<NG, TT, EPI_RESIDUAL>), g, block, 0, stream, k); break;
+        case EPI_SWIGLU: hipLaunchKernelGGL((gemm_multi_kernel<NG, TT, EPI_SWIGLU>), g, block, 0, stream, k); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 // Fast path for up to 8 rows (one row group) when every wave owns exactly NB K-steps of a
 // tile (KS == WAVES * NB): the wave's slice of the activation operand stays in registers
 // for the whole kernel -- it is the same for every tile -- so the only loads in the loop are
@@ -474,16 +611,20 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStre
         SPD_GEMM_CASE(1, 16, 8);
     }
 #undef SPD_GEMM_CASE
-    // More than 5 rows: passes over the weights of up to 4 row groups (20 rows) each.  Every pass
-    // re-reads the matrix, so large batches pay for it; they are functional, not tuned.
-    for (int g0 = 0; g0 < groups; g0 += 4) {
-        const int ng = groups - g0 < 4 ? groups - g0 : 4;
+    // More than 5 rows: passes of up to 8 row groups (40 rows) over the weights.  Tiles are taken three at
+    // a time where that still leaves a tile group for (almost) every CU, or where the matrix is too small to
+    // fill the chip anyway.
+    const bool wide = k.n_tiles >= 3 * 192 || k.n_tiles < 256;
+    for (int g0 = 0; g0 < groups; g0 += 8) {
+        const int ng = groups - g0 < 8 ? groups - g0 : 8;
         k.row0 = g0 * kGroupRows;
         k.rows = a.rows - k.row0 < ng * kGroupRows ? a.rows - k.row0 : ng * kGroupRows;
+        const int tgroups = wide ? (k.n_tiles + 2) / 3 : k.n_tiles;
+        const int mgrid = tgroups < 256 ? tgroups : 256;
         hipError_t e;
-        if (ng == 1) e = (waves == 4) ? launch_epi<1, 4, 8>(k, epilogue, grid, stream) : launch_epi<1, 8, 8>(k, epilogue, grid, stream);
-        else if (ng == 2) e = (waves == 4) ? launch_epi<2, 4, 8>(k, epilogue, grid, stream) : launch_epi<2, 8, 8>(k, epilogue, grid, stream);
-        else e = launch_epi<4, 8, 4>(k, epilogue, grid, stream);   // the epilogue needs 128 threads per row group
+        if (ng <= 2) e = wide ? launch_multi<2, 3>(k, epilogue, mgrid, stream) : launch_multi<2, 1>(k, epilogue, mgrid, stream);
+        else if (ng <= 4) e = wide ? launch_multi<4, 3>(k, epilogue, mgrid, stream) : launch_multi<4, 1>(k, epilogue, mgrid, stream);
+        else e = wide ? launch_multi<8, 3>(k, epilogue, mgrid, stream) : launch_multi<8, 1>(k, epilogue, mgrid, stream);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

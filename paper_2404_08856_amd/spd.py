@@ -154,9 +154,9 @@ class Model:
         torch.cuda.current_stream().synchronize()     # re-tiling done: the caller may drop `weights`
 
     def close(self):
-        if getattr(self, "handle", None):
+        if getattr(self, "handle", None) and _lib is not None:      # _lib is gone at interpreter shutdown
             _lib.spd_model_destroy(self.handle)
-            self.handle = None
+        self.handle = None
 
     def __del__(self):
         self.close()

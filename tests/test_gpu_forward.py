@@ -404,3 +404,27 @@ def test_image_aware_draft_takes_embedding_rows():
         t = int(tok.item())
     assert model.spd_kv_get_len(1) == [12 + 9 + 3]
     model.close()
+
+
+@pytest.mark.parametrize("n_seqs,M", [(2, 4), (3, 7), (8, 8)])
+def test_batched_verify_wide_model(n_seqs, M):
+    """Several row groups on a model whose matrices have 256 and more tiles (d_model 4096): the
+    multi-group projection kernel with one and with three tiles in flight, all three epilogues."""
+    print(f"case batched wide n_seqs={n_seqs} M={M}", flush=True)
+    shape = synth.ModelShape(1, 4096, 2, 128, 3072, 1024)       # gate|up: 384 tiles, O / down: 256 tiles
+    model, wn = build_pair(shape, 57, n_seqs, 48)
+    cfg = oracle_cfg(shape)
+    caches = []
+    for s in range(n_seqs):
+        toks = synth.text_tokens(2 + 5 * s, shape.vocab, 500 + s)
+        c = dec.KVCache(cfg, 48)
+        dec.forward_tokens(cfg, wn, c, toks)
+        caches.append(c)
+        model.spd_prefill_tokens(s, torch.from_numpy(toks).cuda())
+    vt = np.stack([synth.text_tokens(M, shape.vocab, 600 + s) for s in range(n_seqs)])
+    out = torch.empty((n_seqs, M, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_verify_forward(torch.from_numpy(vt).cuda(), out)
+    got = out.cpu().numpy()
+    for s in range(n_seqs):
+        check_logits(got[s], dec.forward_tokens(cfg, wn, caches[s], vt[s]), f"seq {s}")
+    model.close()
