@@ -167,6 +167,7 @@ def side_configs(args, spd, synth, torch):
         abytes = n_seqs * (2 * args.gamma + 1) * V * 4
         per_sigma[str(sigma)] = {"us": us, "GBps": abytes / (us * 1e-6) / 1e9, "mean_accepted": float(k.float().mean())}
     res["block_loop"] = block_loop(args, spd, synth, torch)
+    res["block_loop_batch8_ctx2048"] = block_loop(args, spd, synth, torch, n_seqs=8, n_prefix=2048, graph_too=False)
     res["batched_verify"] = batched_verify(args, spd, synth, torch)
     res["accept_kernel"] = {"workload": f"{n_seqs} sequences x (gamma+1={args.gamma + 1}) rows x vocab {V}, logit inputs, temperature 1; "
                                         "draft logits = target + N(0, sigma^2)",
@@ -175,101 +176,108 @@ def side_configs(args, spd, synth, torch):
     return res
 
 
-def block_loop(args, spd, synth, torch):
+def block_loop(args, spd, synth, torch, n_seqs=1, n_prefix=None, graph_too=True):
     """Whole speculative-decoding blocks (gamma draft steps of the ~110M draft, one 7B target call, accept,
-    commit) with lengths and tokens on the device: back-to-back launches, and one block captured in a graph."""
+    commit) with lengths and tokens on the device: back-to-back launches, and one block captured in a graph.
+    For n_seqs > 1 or a long prefix only sequence lengths are set (zero-filled caches): timing only."""
     M = args.gamma + 1
+    B = n_seqs
     ts, ds = synth.SHAPES["llama7b"], synth.SHAPES["draft_110m"]
-    n_prefix = args.image_rows + args.text_tokens
-    n_blocks = 40
+    real_prefill = n_prefix is None and B == 1
+    if n_prefix is None:
+        n_prefix = args.image_rows + args.text_tokens
+    n_blocks = 40 if B == 1 else 15
     cap = n_prefix + (n_blocks * 2 + 8) * M
-    target = spd.Model(spd.make_config(ts, 1, cap), synth.make_weights(ts, args.seed, device="cuda"))
-    draft = spd.Model(spd.make_config(ds, 1, cap), synth.make_weights(ds, args.seed + 7, device="cuda"))
+    target = spd.Model(spd.make_config(ts, B, cap), synth.make_weights(ts, args.seed, device="cuda"))
+    draft = spd.Model(spd.make_config(ds, B, cap), synth.make_weights(ds, args.seed + 7, device="cuda"))
     torch.cuda.empty_cache()
-    text = torch.from_numpy(synth.text_tokens(args.text_tokens, ts.vocab, args.seed)).cuda()
-    target.spd_prefill(0, torch.from_numpy(synth.image_rows(args.image_rows, ts.d_model, args.seed)).cuda())
-    target.spd_prefill_tokens(0, text)
-    draft.spd_prefill_tokens(0, text[:-1].contiguous())          # the draft re-reads the token before t every block
+    n_text = n_prefix - args.image_rows
+    text = torch.from_numpy(synth.text_tokens(max(n_text, 2), ts.vocab, args.seed)).cuda()
+    if real_prefill:
+        target.spd_prefill(0, torch.from_numpy(synth.image_rows(args.image_rows, ts.d_model, args.seed)).cuda())
+        target.spd_prefill_tokens(0, text)
+        draft.spd_prefill_tokens(0, text[:-1].contiguous())      # the draft re-reads the token before t every block
+    else:
+        target.spd_kv_set_len([n_prefix] * B)
+        draft.spd_kv_set_len([n_text - 1] * B)
     V, g = ts.vocab, args.gamma
-    vt = torch.zeros((1, M), dtype=torch.int32, device="cuda")
-    din = torch.stack([text[-1], torch.tensor(1, dtype=torch.int32, device="cuda")])[None].contiguous()
-    vt[0, 0] = 1
-    D = torch.zeros((1, g, V), dtype=torch.float32, device="cuda")
-    logits = torch.zeros((1, M, V), dtype=torch.float32, device="cuda")
-    ud = torch.from_numpy(synth.uniforms((1, g), args.seed + 20)).cuda()
-    ua = torch.from_numpy(synth.uniforms((1, M), args.seed + 21)).cuda()
-    k = torch.zeros(1, dtype=torch.int32, device="cuda")
-    y = torch.zeros(1, dtype=torch.int32, device="cuda")
-    out = torch.zeros((1, 4096), dtype=torch.int32, device="cuda")
-    n_out = torch.zeros(1, dtype=torch.int32, device="cuda")
-    ws = torch.empty(spd.spd_accept_workspace_bytes(1, g, V), dtype=torch.uint8, device="cuda")
+    vt = torch.ones((B, M), dtype=torch.int32, device="cuda")
+    din = torch.ones((B, 2), dtype=torch.int32, device="cuda")
+    din[:, 0] = text[-1]
+    D = torch.zeros((B, g, V), dtype=torch.float32, device="cuda")
+    logits = torch.zeros((B, M, V), dtype=torch.float32, device="cuda")
+    ud = torch.from_numpy(synth.uniforms((B, g), args.seed + 20)).cuda()
+    ua = torch.from_numpy(synth.uniforms((B, M), args.seed + 21)).cuda()
+    k = torch.zeros(B, dtype=torch.int32, device="cuda")
+    y = torch.zeros(B, dtype=torch.int32, device="cuda")
+    out = torch.zeros((B, 4096), dtype=torch.int32, device="cuda")
+    n_out = torch.zeros(B, dtype=torch.int32, device="cuda")
+    ws = torch.empty(spd.spd_accept_workspace_bytes(B, g, V), dtype=torch.uint8, device="cuda")
     target.spd_kv_lens_to_device()
     draft.spd_kv_lens_to_device()
     vtf, Df, udf = vt.view(-1), D.view(-1), ud.view(-1)
 
     def block():
-        draft.spd_draft_step_strided(din, 2, 1, 2, 1.0, udf, g, Df, g * V, vtf[1:], M)
+        draft.spd_draft_step_strided(din, 2, B, 2, 1.0, udf, g, Df, g * V, vtf[1:], M)
         for j in range(1, g):
-            draft.spd_draft_step_strided(vtf[j:], M, 1, 1, 1.0, udf[j:], g, Df[j * V:], g * V, vtf[j + 1:], M)
+            draft.spd_draft_step_strided(vtf[j:], M, B, 1, 1.0, udf[j:], g, Df[j * V:], g * V, vtf[j + 1:], M)
         target.spd_verify_forward(vt, logits)
         spd.spd_block_finish(target, draft, logits, D, vt, ua, 1.0, k, y, din, out, n_out, ws)
 
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    res = {"workload": f"7B target (prefix {n_prefix}) + draft_110m, gamma={g}, batch 1, temperature 1, random weights "
-                       "(the draft is unrelated to the target: acceptance is whatever two random models give)"}
+    res = {"workload": f"7B target (prefix {n_prefix}) + draft_110m, gamma={g}, batch {B}, temperature 1, random weights "
+                       "(the draft is unrelated to the target: acceptance is whatever two random models give)"
+                       + ("" if real_prefill else "; KV caches zero-filled at the stated lengths (timing only)")}
+
+    def timed(fn):
+        n0 = int(n_out.sum().item())
+        e0.record()
+        for _ in range(n_blocks):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / n_blocks
+        toks = (int(n_out.sum().item()) - n0) / n_blocks
+        return {"ms_per_block": ms, "tokens_per_block": toks, "tokens_per_s": toks / (ms * 1e-3)}
+
     for _ in range(3):
         block()
     torch.cuda.synchronize()
-    n0 = int(n_out.item())
-    e0.record()
-    for _ in range(n_blocks):
-        block()
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / n_blocks
-    n1 = int(n_out.item())
-    res["eager"] = {"ms_per_block": ms, "tokens_per_block": (n1 - n0) / n_blocks, "tokens_per_s": (n1 - n0) / n_blocks / (ms * 1e-3)}
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        block()
-    torch.cuda.current_stream().wait_stream(side)
-    torch.cuda.synchronize()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        block()
-    torch.cuda.synchronize()
-    n0 = int(n_out.item())
-    e0.record()
-    for _ in range(n_blocks):
-        graph.replay()
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / n_blocks
-    n1 = int(n_out.item())
-    res["graph"] = {"ms_per_block": ms, "tokens_per_block": (n1 - n0) / n_blocks, "tokens_per_s": (n1 - n0) / n_blocks / (ms * 1e-3)}
+    res["eager"] = timed(block)
+    if graph_too:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            block()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            block()
+        torch.cuda.synchronize()
+        res["graph"] = timed(graph.replay)
     # the same uniforms every block: the figures are about time, not about acceptance statistics
     target.spd_kv_lens_from_device()
     draft.spd_kv_lens_from_device()
-    # target-only autoregressive decoding with the same kernels (one token per target call, sampled on the
-    # device): the baseline of the paper's speed-up (Section 4, metrics)
-    target.spd_kv_set_len([n_prefix])
-    Drow = torch.zeros((1, V), dtype=torch.float32, device="cuda")
-    tok = torch.ones((1,), dtype=torch.int32, device="cuda")
-    u1 = ud.view(-1)[:1]
+    # target-only autoregressive decoding with the same kernels (one token per sequence and target call,
+    # sampled on the device): the baseline of the paper's speed-up (Section 4, metrics)
+    target.spd_kv_set_len([n_prefix] * B)
+    Drow = torch.zeros((B, V), dtype=torch.float32, device="cuda")
+    tok = torch.ones((B,), dtype=torch.int32, device="cuda")
+    u1 = ud[:, 0].contiguous()
     for _ in range(3):
-        target.spd_draft_step(tok.view(1, 1), 1.0, u1, Drow, tok)
+        target.spd_draft_step(tok.view(B, 1), 1.0, u1, Drow, tok)
     torch.cuda.synchronize()
     e0.record()
     for _ in range(n_blocks):
-        target.spd_draft_step(tok.view(1, 1), 1.0, u1, Drow, tok)
+        target.spd_draft_step(tok.view(B, 1), 1.0, u1, Drow, tok)
     e1.record()
     torch.cuda.synchronize()
     ar_ms = e0.elapsed_time(e1) / n_blocks
-    res["autoregressive"] = {"ms_per_token": ar_ms, "tokens_per_s": 1e3 / ar_ms}
+    res["autoregressive"] = {"ms_per_step": ar_ms, "tokens_per_s": B * 1e3 / ar_ms}
     blk = res["eager"]["ms_per_block"]
     res["speedup_over_autoregressive"] = {
-        "measured_random_pair": res["eager"]["tokens_per_s"] * ar_ms * 1e-3,
+        "measured_random_pair": res["eager"]["tokens_per_s"] / res["autoregressive"]["tokens_per_s"],
         "at_block_efficiency": {str(tau): tau * ar_ms / blk for tau in (2.0, 2.5, 3.0)},
         "note": "block time and AR step time are measured; tokens per block of a trained draft are not available here, "
                 "so the speed-up is also given for block efficiencies around what the paper reports for its trained drafts "
