@@ -47,12 +47,8 @@ __device__ __forceinline__ f32x4_t mfma16(const uint4 &a, const uint4 &b, f32x4_
                                                    __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
-// x rounded to the nearest bf16 (ties to even), as a float; x finite
-__device__ __forceinline__ float rne_bf16(float x) {
-    uint32_t b = __float_as_uint(x);
-    b += 0x7fffu + ((b >> 16) & 1u);
-    return __uint_as_float(b & 0xffff0000u);
-}
+// x rounded to the nearest bf16 (ties to even), as a float
+__device__ __forceinline__ float rne_bf16(float x) { return bf16_bits_to_f32(f32_to_bf16_bits(x)); }
 
 __device__ __forceinline__ uint32_t pack2(uint16_t lo, uint16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
 
@@ -221,12 +217,12 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
             for (int ab = 0; ab < 2; ++ab)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const float p = expf(sv[ab][v] - m_new);           // exp(-inf) = 0 for masked keys
+                    const float p = sv[ab][v] == -INFINITY ? 0.f : exp_neg(sv[ab][v] - m_new);   // masked keys: 0
                     lsum += p;
                     // this lane's column carries term r / 5 of query r % 5: p, p - t0 or p - t0 - t1
                     const float r1 = p - rne_bf16(p);
                     const float r2 = r1 - rne_bf16(r1);
-                    hv[4 * ab + v] = __float_as_uint(rne_bf16(sel0 * p + sel1 * r1 + sel2 * r2)) >> 16;
+                    hv[4 * ab + v] = f32_to_bf16_bits(sel0 * p + sel1 * r1 + sel2 * r2);
                 }
             const uint4 pb = uint4{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16), hv[4] | (hv[5] << 16), hv[6] | (hv[7] << 16)};
             lsum += __shfl_xor(lsum, 16);

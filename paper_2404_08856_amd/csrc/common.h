@@ -16,12 +16,21 @@ constexpr int kTerms = 3;      // bf16 terms per activation value
 constexpr int kMaxRows = 64;
 constexpr int kMaxGroups = (kMaxRows + kGroupRows - 1) / kGroupRows;
 
-// float32 -> bfloat16 bits, round to nearest even (NaN -> quiet NaN).
+// float32 -> bfloat16 bits, round to nearest even (NaN stays NaN): the conversion instruction of
+// gfx950 (v_cvt_pk_bf16_f32; checked bit for bit against the integer formula
+// (b + 0x7fff + ((b >> 16) & 1)) >> 16 on 2^24 random patterns, every exact tie, denormals and infinities).
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
-    uint32_t b = __float_as_uint(f);
-    if ((b & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
-    b += 0x7fffu + ((b >> 16) & 1u);
-    return (uint16_t)(b >> 16);
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
+}
+// exp(x) for x <= 0 through the hardware base-2 exponential, with the rounding error of
+// x * log2(e) carried along (about 2 ulp overall); arguments below -87 give (nearly) 0.
+__device__ __forceinline__ float exp_neg(float x) {
+    x = fmaxf(x, -87.0f);
+    const float c1 = 1.44269502162933349609375f, c2 = 1.925963033500011e-8f;   // log2(e) = c1 + c2
+    const float t = x * c1;
+    const float lo = __builtin_fmaf(x, c1, -t) + x * c2;
+    const float p = __builtin_amdgcn_exp2f(t);
+    return __builtin_fmaf(p, lo * 0.693147180559945f, p);
 }
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) {
     return __uint_as_float(((uint32_t)h) << 16);
