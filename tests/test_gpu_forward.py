@@ -428,3 +428,30 @@ def test_batched_verify_wide_model(n_seqs, M):
     for s in range(n_seqs):
         check_logits(got[s], dec.forward_tokens(cfg, wn, caches[s], vt[s]), f"seq {s}")
     model.close()
+
+
+@pytest.mark.parametrize("slices", [1, 2, 4, 8])
+def test_attention_head_slicing_variants(slices, monkeypatch):
+    """Every way of cutting a 128-wide head over workgroups (1, 2, 4 or 8 slices; chosen by batch
+    size in production) gives the same attention: forced here on a 3-sequence batch with 7 rows each
+    (two attention launches per layer) and on a single sequence without the fused kernel."""
+    monkeypatch.setenv("SPD_ATTN_SLICES", str(slices))
+    monkeypatch.setenv("SPD_NO_FUSE", "1")
+    shape = synth.ModelShape(1, 4096, 2, 128, 256, 1024)
+    print(f"case slices={slices}", flush=True)
+    model, wn = build_pair(shape, 61, 3, 100)
+    cfg = oracle_cfg(shape)
+    caches = []
+    for s in range(3):
+        toks = synth.text_tokens(33 + 29 * s, shape.vocab, 700 + s)      # 33, 62, 91 cached positions
+        c = dec.KVCache(cfg, 100)
+        dec.forward_tokens(cfg, wn, c, toks)
+        caches.append(c)
+        model.spd_prefill_tokens(s, torch.from_numpy(toks).cuda())
+    vt = np.stack([synth.text_tokens(7, shape.vocab, 800 + s) for s in range(3)])
+    out = torch.empty((3, 7, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_verify_forward(torch.from_numpy(vt).cuda(), out)
+    got = out.cpu().numpy()
+    for s in range(3):
+        check_logits(got[s], dec.forward_tokens(cfg, wn, caches[s], vt[s]), f"seq {s}")
+    model.close()
