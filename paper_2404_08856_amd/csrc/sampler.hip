@@ -170,12 +170,17 @@ __device__ void row_stats_regs(const float4 (&v)[kRowVec], int V, float inv_temp
         int oa = __shfl_xor(arg, off);
         if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
     }
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = kSampThreads >> 6;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     if (lane == 0) { s_mx[w] = mx; s_arg[w] = arg; }
     __syncthreads();
-    mx = s_mx[0]; arg = s_arg[0];
-    for (int i = 1; i < nw; ++i)
-        if (s_mx[i] > mx || (s_mx[i] == mx && s_arg[i] < arg)) { mx = s_mx[i]; arg = s_arg[i]; }
+    static_assert(kSampThreads / 64 == 16, "the cross-wave steps below combine 16 partials in 16 lanes");
+    mx = s_mx[lane & 15]; arg = s_arg[lane & 15];             // 16 wave results, combined by every 16-lane group
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) {
+        float om = __shfl_xor(mx, off);
+        int oa = __shfl_xor(arg, off);
+        if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
+    }
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < kRowVec; ++i) {                       // padding is -inf: exp gives 0
@@ -188,11 +193,10 @@ __device__ void row_stats_regs(const float4 (&v)[kRowVec], int V, float inv_temp
     for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
     if (lane == 0) s_sum[w] = sum;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        float t = 0.f;
-        for (int i = 0; i < nw; ++i) t += s_sum[i];
-        out_shared->mx = mx; out_shared->sum = t; out_shared->argmax = arg; out_shared->pad = 0;
-    }
+    float t = s_sum[lane & 15];                               // fixed tree over the 16 wave sums
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) t += __shfl_xor(t, off);
+    if (threadIdx.x == 0) { out_shared->mx = mx; out_shared->sum = t; out_shared->argmax = arg; out_shared->pad = 0; }
     __syncthreads();
 }
 
@@ -230,12 +234,23 @@ __device__ int sample_inverse_cdf_regs(WF wf, int V, float u, unsigned long long
         for (int i = 0; i < kRowVec; ++i) tmp[i * 17 + w] = incl[i];
     }
     __syncthreads();
-    if (threadIdx.x == 0) {                                   // slices in order, waves in order
-        unsigned long long run = 0;
-        for (int i = 0; i < kRowVec; ++i)
-            for (int k = 0; k < kSampThreads / 64; ++k) { unsigned long long t = tmp[i * 17 + k]; tmp[i * 17 + k] = run; run += t; }
-        tmp[16] = run;                                        // slot 16 of slice 0 is free
-        *result = -1;
+    // exclusive scan of the kRowVec x 16 wave totals (slices in order, waves in order) by wave 0:
+    // two neighbouring entries per lane, integer sums, so the order of combination does not matter
+    static_assert(kRowVec * (kSampThreads / 64) == 128, "one wave, two entries per lane");
+    if (w == 0) {
+        const int n0 = 2 * lane, n1 = 2 * lane + 1;
+        const int a0 = (n0 >> 4) * 17 + (n0 & 15), a1 = (n1 >> 4) * 17 + (n1 & 15);
+        const unsigned long long v0 = tmp[a0], v1 = tmp[a1];
+        unsigned long long inc = v0 + v1;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            unsigned long long t = shfl_up_u64(inc, off);
+            if (lane >= off) inc += t;
+        }
+        const unsigned long long excl = inc - v0 - v1;
+        tmp[a0] = excl;
+        tmp[a1] = excl + v0;
+        if (lane == 63) { tmp[16] = inc; *result = -1; }      // slot 16 of slice 0 is free: the grand total
     }
     __syncthreads();
     const unsigned long long S = tmp[16];
