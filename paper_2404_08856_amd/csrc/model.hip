@@ -50,7 +50,7 @@ struct Layout {                    // byte offsets inside the three buffers
     int v_stride;
     // workspace
     size_t h, qkv, xn, xo, xf, rope, logits, ssq_a, ssq_b, d_lens, d_error, qa_count, qa_abort, ws_total;
-    size_t m_hg, m_att, m_xf, m_ssq_a, m_ssq_b, m_sync, m_clock;     // arrays of the whole-forward kernel (8 rows)
+    size_t m_hg, m_att, m_xf, m_ssq_a, m_ssq_b, m_sync, m_clock;     // arrays of the whole-forward kernel (one row group)
 };
 
 int32_t check_shape(const spd_model_config &c) {
@@ -296,7 +296,7 @@ int32_t spd_model_create(const spd_model_config *cfg, const spd_weights *w, void
     m->t_gu = default_tuning(2 * F, d);     env_tuning("gu", m->t_gu);
     m->t_down = default_tuning(d, F);       env_tuning("down", m->t_down);
     m->t_lm = default_tuning(V, d);         env_tuning("lm", m->t_lm);
-    // Whole-forward persistent kernel for calls of up to 8 rows.  Opt-in (SPD_MEGA=1): at the 7B
+    // Whole-forward persistent kernel for calls of up to 5 rows.  Opt-in (SPD_MEGA=1): at the 7B
     // shape its device-wide barriers and lock-step stages currently cost more than the launch
     // gaps of the per-stage kernels they remove, so the per-stage path is the default.
     // fused QKV + attention (SPD_NO_FUSE=1 keeps the two kernels)
