@@ -121,7 +121,7 @@ int32_t spd_kv_get_len(const spd_model *model, int32_t *h_len_per_seq, int32_t n
  * e.g. [V_1..V_m ; E[X_1..X_n]] for the target, Section 2.2 Eq. 1) to sequence
  * `seq` starting at its current KV length, appending their K, V.  If
  * last_logits != NULL it receives the float32 logits [vocab] of the last row.
- * Runs the same kernels as the verify step, 5 rows per pass. */
+ * Runs the same kernels as a batched verify step, 40 rows per pass. */
 int32_t spd_prefill(spd_model *model, int32_t seq, const float *embeds, int32_t n_rows,
                     float *last_logits, void *stream);
 

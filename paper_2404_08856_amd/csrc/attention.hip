@@ -13,7 +13,7 @@ __global__ __launch_bounds__(AW * 64) void attention_kernel(AttnArgs a) {
 }
 
 hipError_t launch_attention(const AttnArgs &a, hipStream_t stream) {
-    if (a.M < 1 || a.M > 8 || (a.v_stride % 32) != 0 || a.v_stride < a.max_positions) return hipErrorInvalidValue;
+    if (a.M < 1 || a.M > kMaxRows || (a.v_stride % 32) != 0 || a.v_stride < a.max_positions) return hipErrorInvalidValue;
     if (a.Mq < 1 || a.Mq > kGroupRows || a.m0 < 0 || a.m0 + a.Mq > a.M || a.M > a.max_positions) return hipErrorInvalidValue;
     // Workgroups per head (slices of the head dimension).  One sequence: 16 output dimensions per
     // workgroup is fastest at the 7B shape (15.4 us per layer against 16.2 with 32 and 18.8 with 64).

@@ -373,12 +373,13 @@ namespace {
 
 // One decoder forward over M new rows for sequences seq0 .. seq0 + n_seqs - 1.
 // Input rows come from token ids (embedding gather) or from embedding rows.
+// max_m: SPD_MAX_M for the public calls; the prefill feeds one sequence up to 40 rows (8 row groups) per pass.
 int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const float *embeds, int seq0, int n_seqs, int M,
-                float *logits_out, hipStream_t st) {
+                float *logits_out, hipStream_t st, int max_m = SPD_MAX_M) {
     const spd_model_config &c = m->cfg;
     const Layout &L = m->L;
     const int rows = n_seqs * M;
-    if (M < 1 || M > SPD_MAX_M) return fail(SPD_ERR_SHAPE, "M = %d must be in 1..%d", M, SPD_MAX_M);
+    if (M < 1 || M > max_m) return fail(SPD_ERR_SHAPE, "M = %d must be in 1..%d", M, max_m);
     if (n_seqs < 1 || rows > SPD_MAX_ROWS) return fail(SPD_ERR_SHAPE, "n_seqs * M = %d must be in 1..%d", rows, SPD_MAX_ROWS);
     if (seq0 < 0 || seq0 + n_seqs > c.max_seqs) return fail(SPD_ERR_CAPACITY, "sequence index beyond max_seqs %d", c.max_seqs);
     if (M > c.max_positions) return fail(SPD_ERR_CAPACITY, "M = %d exceeds max_positions %d", M, c.max_positions);
@@ -499,11 +500,12 @@ int32_t prefill_common(spd_model *m, int32_t seq, const float *embeds, const int
     if (m->lens[seq] + n_rows > m->cfg.max_positions)
         return fail(SPD_ERR_CAPACITY, "KV cache overflow in prefill: %d + %d > %d", m->lens[seq], n_rows, m->cfg.max_positions);
     float *scratch = (float *)(m->ws + m->L.logits);
-    for (int r0 = 0; r0 < n_rows; r0 += kGroupRows) {        // one row group per pass: the single-group kernels
-        int M = n_rows - r0 < kGroupRows ? n_rows - r0 : kGroupRows;
+    const int pass_rows = 8 * kGroupRows;                    // 8 row groups: one pass over the weights per 40 rows
+    for (int r0 = 0; r0 < n_rows; r0 += pass_rows) {
+        int M = n_rows - r0 < pass_rows ? n_rows - r0 : pass_rows;
         bool last = r0 + M >= n_rows;
         int32_t rc = forward(m, tokens ? tokens + r0 : nullptr, M, embeds ? embeds + (size_t)r0 * m->cfg.d_model : nullptr,
-                             seq, 1, M, (last && last_logits) ? scratch : nullptr, st);
+                             seq, 1, M, (last && last_logits) ? scratch : nullptr, st, pass_rows);
         if (rc) return rc;
         if (last && last_logits)
             HIP_TRY(hipMemcpyAsync(last_logits, scratch + (size_t)(M - 1) * m->cfg.vocab, (size_t)m->cfg.vocab * 4,
