@@ -222,7 +222,7 @@ def setup_device_loop(n_seqs, gamma, n_blocks, temperature, seed, m_img):
     spd = spd_mod()
     t_shape, d_shape = synth.SHAPES["tiny_target"], synth.SHAPES["tiny_draft"]
     V = t_shape.vocab
-    cap = m_img + 40 + n_blocks * (gamma + 1) + 8
+    cap = m_img + 12 + 9 * n_seqs + n_blocks * (gamma + 1) + 8
     tw = randomize_gains(synth.make_weights(t_shape, seed))
     dw = randomize_gains(synth.make_weights(d_shape, seed + 50), seed=5)
     target = spd.Model(spd.make_config(t_shape, n_seqs, cap), to_device(tw))
@@ -295,7 +295,7 @@ def check_block_against_oracle(loop, oracle, models, u_draft_b, u_accept_b, b):
     return ks
 
 
-@pytest.mark.parametrize("n_seqs,gamma", [(1, 4), (3, 3)])
+@pytest.mark.parametrize("n_seqs,gamma", [(1, 4), (3, 3), (2, 5), (8, 7)])
 def test_device_block_loop_lockstep(n_seqs, gamma):
     """No host decision between blocks: lengths, tokens and the commit stay on the device."""
     n_blocks, temperature, seed = 6, 1.0, 31
