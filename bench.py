@@ -167,7 +167,7 @@ def side_configs(args, spd, synth, torch):
         abytes = n_seqs * (2 * args.gamma + 1) * V * 4
         per_sigma[str(sigma)] = {"us": us, "GBps": abytes / (us * 1e-6) / 1e9, "mean_accepted": float(k.float().mean())}
     res["block_loop"] = block_loop(args, spd, synth, torch)
-    res["block_loop_batch8_ctx2048"] = block_loop(args, spd, synth, torch, n_seqs=8, n_prefix=2048, graph_too=False)
+    res["block_loop_batch8_ctx2048"] = block_loop(args, spd, synth, torch, n_seqs=8, n_prefix=2048, graph_too=False, projected=True)
     res["batched_verify"] = batched_verify(args, spd, synth, torch)
     res["accept_kernel"] = {"workload": f"{n_seqs} sequences x (gamma+1={args.gamma + 1}) rows x vocab {V}, logit inputs, temperature 1; "
                                         "draft logits = target + N(0, sigma^2)",
@@ -176,7 +176,7 @@ def side_configs(args, spd, synth, torch):
     return res
 
 
-def block_loop(args, spd, synth, torch, n_seqs=1, n_prefix=None, graph_too=True):
+def block_loop(args, spd, synth, torch, n_seqs=1, n_prefix=None, graph_too=True, projected=False):
     """Whole speculative-decoding blocks (gamma draft steps of the ~110M draft, one 7B target call, accept,
     commit) with lengths and tokens on the device: back-to-back launches, and one block captured in a graph.
     For n_seqs > 1 or a long prefix only sequence lengths are set (zero-filled caches): timing only."""
@@ -188,8 +188,12 @@ def block_loop(args, spd, synth, torch, n_seqs=1, n_prefix=None, graph_too=True)
         n_prefix = args.image_rows + args.text_tokens
     n_blocks = 40 if B == 1 else 15
     cap = n_prefix + (n_blocks * 2 + 8) * M
-    target = spd.Model(spd.make_config(ts, B, cap), synth.make_weights(ts, args.seed, device="cuda"))
-    draft = spd.Model(spd.make_config(ds, B, cap), synth.make_weights(ds, args.seed + 7, device="cuda"))
+    tw = synth.make_weights(ts, args.seed, device="cuda")
+    # draft: independent random weights, or the target's first 12 layers projected to the draft's width
+    dw = synth.projected_draft(tw, ts, ds, args.seed + 7) if projected else synth.make_weights(ds, args.seed + 7, device="cuda")
+    target = spd.Model(spd.make_config(ts, B, cap), tw)
+    draft = spd.Model(spd.make_config(ds, B, cap), dw)
+    del tw, dw
     torch.cuda.empty_cache()
     n_text = n_prefix - args.image_rows
     text = torch.from_numpy(synth.text_tokens(max(n_text, 2), ts.vocab, args.seed)).cuda()
@@ -225,8 +229,10 @@ def block_loop(args, spd, synth, torch, n_seqs=1, n_prefix=None, graph_too=True)
         spd.spd_block_finish(target, draft, logits, D, vt, ua, 1.0, k, y, din, out, n_out, ws)
 
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    res = {"workload": f"7B target (prefix {n_prefix}) + draft_110m, gamma={g}, batch {B}, temperature 1, random weights "
-                       "(the draft is unrelated to the target: acceptance is whatever two random models give)"
+    res = {"workload": f"7B target (prefix {n_prefix}) + draft_110m, gamma={g}, batch {B}, temperature 1, random target weights, "
+                       + ("draft = the target's first 12 layers projected to d=768 by fixed random orthogonal maps"
+                          if projected else "independent random draft")
+                       + " (acceptance is whatever such a pair gives; it is measured, not designed)"
                        + ("" if real_prefill else "; KV caches zero-filled at the stated lengths (timing only)")}
 
     def timed(fn):

@@ -115,6 +115,43 @@ def make_weights(shape, seed, std=0.02, device="cpu"):
     return w
 
 
+def projected_draft(target_weights, target_shape, draft_shape, seed):
+    """A draft whose weights are the target's first layers seen through fixed random orthogonal maps
+    (the full-loop benchmark configuration's draft): with R [d_t, d_d] and S [F_t, F_d] of
+    orthonormal columns (QR of seeded Gaussians), Wq' = R^T Wq R (likewise Wk, Wv, Wo),
+    Wgate' = S^T Wgate R (likewise Wup), Wdown' = R^T Wdown S, E' = E R (tied head), gains 1,
+    everything rounded to bf16; the draft's head structure is imposed on the projected
+    matrices as they are.  Input tensors may live on any device; the result lives there too.
+    """
+    dev = target_weights["embed"].device
+    dt, dd, Ft, Fd = target_shape.d_model, draft_shape.d_model, target_shape.d_ffn, draft_shape.d_ffn
+    assert target_shape.n_heads * target_shape.head_dim == dt and draft_shape.n_heads * draft_shape.head_dim == dd
+    assert draft_shape.tied_embeddings and draft_shape.vocab == target_shape.vocab
+    assert draft_shape.n_layers <= target_shape.n_layers
+
+    def ortho(rows, cols, name):
+        g = torch.Generator().manual_seed(_tensor_seed(seed, name, -1))
+        q, _ = torch.linalg.qr(torch.randn((rows, cols), generator=g, dtype=torch.float64))
+        return q.to(torch.float32).to(dev)
+
+    R, S = ortho(dt, dd, "proj_R"), ortho(Ft, Fd, "proj_S")
+    f = lambda t: t.to(torch.float32)
+    b = lambda t: t.to(torch.bfloat16).contiguous()
+    w = {"embed": b(f(target_weights["embed"]) @ R), "lm_head": None,
+         "final_norm": torch.ones(dd, dtype=torch.float32, device=dev), "layers": []}
+    for l in range(draft_shape.n_layers):
+        lw = target_weights["layers"][l]
+        w["layers"].append({
+            "attn_norm": torch.ones(dd, dtype=torch.float32, device=dev),
+            "wq": b(R.T @ f(lw["wq"]) @ R), "wk": b(R.T @ f(lw["wk"]) @ R), "wv": b(R.T @ f(lw["wv"]) @ R),
+            "wo": b(R.T @ f(lw["wo"]) @ R),
+            "mlp_norm": torch.ones(dd, dtype=torch.float32, device=dev),
+            "w_gate": b(S.T @ f(lw["w_gate"]) @ R), "w_up": b(S.T @ f(lw["w_up"]) @ R),
+            "w_down": b(R.T @ f(lw["w_down"]) @ S),
+        })
+    return w
+
+
 def bf16_bits(t):
     """bf16 torch tensor -> numpy uint16 array of its bit patterns (host)."""
     return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
