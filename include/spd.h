@@ -24,7 +24,9 @@
  *     error of the calling thread.
  *   - Pointers are DEVICE pointers unless the name starts with h_ (host).
  *   - All device work is enqueued on the caller's hipStream_t, passed as void*
- *     (NULL = the default stream).  No call synchronises the device.
+ *     (NULL = the default stream).  No call synchronises the device, except the few
+ *     whose comment says so (spd_kv_lens_to_device / _from_device, spd_device_status,
+ *     spd_trace_read, spd_trace_stages).
  *   - The library allocates no device memory: weights (packed), KV cache and
  *     workspace live in caller-owned buffers whose sizes spd_model_bytes()
  *     reports.  The model borrows them until spd_model_destroy().
