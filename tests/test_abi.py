@@ -57,3 +57,31 @@ def test_accept_workspace_bytes_and_argument_checks():
     with pytest.raises(spd.SpdError) as e:
         spd.spd_accept_workspace_bytes(0, 4, 32000)
     assert e.value.code == spd.SPD_ERR_INVALID_ARG
+
+
+def test_binding_fails_loudly_without_the_library(tmp_path):
+    """No CPU fallback: a copy of the package without libspd.so cannot even be imported."""
+    import shutil
+    import subprocess
+    import sys
+    pkg = os.path.join(ROOT, "paper_2404_08856_amd")
+    dst = tmp_path / "paper_2404_08856_amd"
+    dst.mkdir()
+    for name in ("__init__.py", "spd.py", "synth.py"):
+        shutil.copy(os.path.join(pkg, name), dst / name)
+    r = subprocess.run([sys.executable, "-c", "import paper_2404_08856_amd.spd"], cwd=tmp_path, capture_output=True, text=True,
+                       timeout=300, env={**os.environ, "PYTHONPATH": str(tmp_path)})
+    assert r.returncode != 0 and "ImportError" in r.stderr and "libspd.so is missing" in r.stderr
+
+
+def test_product_does_not_import_the_oracle():
+    """The oracle is test infrastructure: nothing under the package (or the bench's GPU path) imports it."""
+    import re
+    pkg = os.path.join(ROOT, "paper_2404_08856_amd")
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            text = open(os.path.join(pkg, name)).read()
+            assert not re.search(r"^\s*(from|import)\s+oracle\b", text, re.M), name
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    uses = [m.start() for m in re.finditer(r"from oracle import", bench)]
+    assert len(uses) == 1 and "def cpu_baseline" in bench[:uses[0]] and "def side_configs" not in bench[:uses[0]]

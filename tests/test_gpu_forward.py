@@ -455,3 +455,29 @@ def test_attention_head_slicing_variants(slices, monkeypatch):
     for s in range(3):
         check_logits(got[s], dec.forward_tokens(cfg, wn, caches[s], vt[s]), f"seq {s}")
     model.close()
+
+
+def test_tracing_counts_every_launch_group():
+    """spd_trace_read: per-kind launch counts of a traced forward (the figures bench.py's roofline uses)."""
+    spd = spd_mod()
+    shape = synth.SHAPES["tiny_target"]                 # 2 layers; d_model 256: QKV + attention take separate kernels
+    model, _ = build_pair(shape, 71, 1, 64)
+    model.spd_prefill_tokens(0, torch.from_numpy(synth.text_tokens(9, shape.vocab, 71)).cuda())
+    vt = torch.from_numpy(synth.text_tokens(5, shape.vocab, 72)).cuda()[None].contiguous()
+    out = torch.empty((1, 5, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_trace_enable(True)
+    model.spd_verify_forward(vt, out)
+    model.spd_verify_forward(vt, out)
+    tr = model.spd_trace_read()
+    assert set(tr) == set(spd.TRACE_KINDS)
+    L = shape.n_layers
+    counts = {k: n for k, (ms, n) in tr.items()}
+    assert counts["qkv"] == 2 * L and counts["attention"] == 2 * L and counts["o"] == 2 * L
+    assert counts["gate_up"] == 2 * L and counts["down"] == 2 * L and counts["lm_head"] == 2 and counts["embed"] == 2
+    assert counts["forward"] == 0
+    assert all(ms > 0 for k, (ms, n) in tr.items() if n)
+    assert all(n == 0 for ms, n in model.spd_trace_read().values())        # reading forgets
+    model.spd_trace_enable(False)
+    model.spd_verify_forward(vt, out)
+    assert all(n == 0 for ms, n in model.spd_trace_read().values())
+    model.close()
