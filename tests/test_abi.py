@@ -85,3 +85,35 @@ def test_product_does_not_import_the_oracle():
     bench = open(os.path.join(ROOT, "bench.py")).read()
     uses = [m.start() for m in re.finditer(r"from oracle import", bench)]
     assert len(uses) == 1 and "def cpu_baseline" in bench[:uses[0]] and "def side_configs" not in bench[:uses[0]]
+
+
+def test_null_handles_are_refused_by_every_entry_point():
+    """Host-side argument validation: a NULL model (or buffer) is an error code and a message, never a crash."""
+    from paper_2404_08856_amd import spd
+    lib = ctypes.CDLL(spd.LIB_PATH)
+    lib.spd_last_error.restype = ctypes.c_char_p
+    null = ctypes.c_void_p(None)
+    i32, f32, sz = ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+    calls = {
+        "spd_kv_set_len": (null, null, i32(1)),
+        "spd_kv_get_len": (null, null, i32(1)),
+        "spd_kv_lens_to_device": (null, null),
+        "spd_kv_lens_from_device": (null, null),
+        "spd_device_status": (null, null),
+        "spd_prefill": (null, i32(0), null, i32(1), null, null),
+        "spd_prefill_tokens": (null, i32(0), null, i32(1), null, null),
+        "spd_verify_forward": (null, null, i32(1), i32(5), null, null),
+        "spd_draft_step": (null, null, i32(1), i32(1), f32(1.0), null, null, null, null),
+        "spd_draft_step_strided": (null, null, i32(1), i32(1), i32(1), f32(1.0), null, i32(1), null, sz(16), null, i32(1), null),
+        "spd_speculative_accept": (null, null, null, null, i32(1), i32(4), i32(16), f32(1.0), ctypes.c_uint32(0), null, null, null, null, sz(0), null),
+        "spd_block_finish": (null, null, null, null, null, null, i32(1), i32(4), f32(1.0), null, null, null, null, i32(0), null, null, sz(0), null),
+        "spd_trace_enable": (null, i32(1)),
+        "spd_trace_read": (null, i32(8), null, null),
+        "spd_trace_stages": (null, i32(8), null, null, null, null, null),
+    }
+    for name, args in calls.items():
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int32
+        rc = fn(*args)
+        assert rc == spd.SPD_ERR_INVALID_ARG, (name, rc)
+        assert lib.spd_last_error(), name
