@@ -521,13 +521,13 @@ static hipError_t launch_regb(const GemmKernelArgs &k, int epilogue, int grid, h
     dim3 g(grid), block(WAVES * 64);
     switch (epilogue) {
         case EPI_STORE:
-            hipLaunchKernelGGL((gemm_regb_kernel<WAVES, EPI_STORE, NB, U>), g, block, 0, stream, k);
+            launch_kernel(gemm_regb_kernel<WAVES, EPI_STORE, NB, U>, g, block, stream, k);
             break;
         case EPI_RESIDUAL:
-            hipLaunchKernelGGL((gemm_regb_kernel<WAVES, EPI_RESIDUAL, NB, U>), g, block, 0, stream, k);
+            launch_kernel(gemm_regb_kernel<WAVES, EPI_RESIDUAL, NB, U>, g, block, stream, k);
             break;
         case EPI_SWIGLU:
-            hipLaunchKernelGGL((gemm_regb_kernel<WAVES, EPI_SWIGLU, NB, U>), g, block, 0, stream, k);
+            launch_kernel(gemm_regb_kernel<WAVES, EPI_SWIGLU, NB, U>, g, block, stream, k);
             break;
         default:
             return hipErrorInvalidValue;
@@ -540,13 +540,13 @@ static hipError_t launch_epi(const GemmKernelArgs &k, int epilogue, int grid, hi
     dim3 g(grid), block(WAVES * 64);
     switch (epilogue) {
         case EPI_STORE:
-            hipLaunchKernelGGL((gemm_stream_kernel<NG, WAVES, EPI_STORE, U>), g, block, 0, stream, k);
+            launch_kernel(gemm_stream_kernel<NG, WAVES, EPI_STORE, U>, g, block, stream, k);
             break;
         case EPI_RESIDUAL:
-            hipLaunchKernelGGL((gemm_stream_kernel<NG, WAVES, EPI_RESIDUAL, U>), g, block, 0, stream, k);
+            launch_kernel(gemm_stream_kernel<NG, WAVES, EPI_RESIDUAL, U>, g, block, stream, k);
             break;
         case EPI_SWIGLU:
-            hipLaunchKernelGGL((gemm_stream_kernel<NG, WAVES, EPI_SWIGLU, U>), g, block, 0, stream, k);
+            launch_kernel(gemm_stream_kernel<NG, WAVES, EPI_SWIGLU, U>, g, block, stream, k);
             break;
         default:
             return hipErrorInvalidValue;

@@ -6,7 +6,27 @@
 
 #include "common.h"
 
+#include <hip/hip_ext.h>
+
 namespace spd {
+
+// ---- per-kernel timing (tracing) ---------------------------------------------------
+// While *launch_timing() points at a pair of events, the single-kernel launch wrappers below hand
+// them to the launch itself, so that they time the kernel alone (start of execution to completion,
+// what a profiler reports) instead of the interval between two events recorded around the launch.
+struct LaunchTiming { hipEvent_t start, stop; bool used; };
+LaunchTiming *&launch_timing();                    // thread-local; NULL: plain launches
+
+template <class Kernel, class... Args>
+inline void launch_kernel(Kernel kernel, dim3 grid, dim3 block, hipStream_t stream, Args... args) {
+    LaunchTiming *t = launch_timing();
+    if (t && !t->used) {
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, t->start, t->stop, 0, args...);
+        t->used = true;
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
+    }
+}
 
 // ---- weight re-tiling (model creation) ------------------------------------------
 enum PackMode { PACK_PLAIN = 0, PACK_CONCAT3 = 1, PACK_GATE_UP = 2 };

@@ -189,7 +189,8 @@ struct spd_model {
 namespace {
 enum ProfKind { PK_QKV = 0, PK_O, PK_GATE_UP, PK_DOWN, PK_LM_HEAD, PK_ATTENTION, PK_FORWARD, PK_EMBED, PK_COUNT };
 
-// Runs one launch; when tracing is on, brackets it with events on the same stream.
+// Runs one launch group; when tracing is on, brackets it with events on the same stream (the interval
+// then includes the dispatch of the group's first kernel).
 #define PROF_TRY(kind, expr)                                                                   \
     do {                                                                                       \
         spd_model::Span sp_{(kind), nullptr, nullptr};                                         \
@@ -201,7 +202,42 @@ enum ProfKind { PK_QKV = 0, PK_O, PK_GATE_UP, PK_DOWN, PK_LM_HEAD, PK_ATTENTION,
         HIP_TRY(expr);                                                                         \
         if (m->prof_on) { HIP_TRY(hipEventRecord(sp_.b, st)); m->spans.push_back(sp_); }       \
     } while (0)
+
+// Same for a group that is a single kernel whose launch wrapper can hand the two events to the launch
+// itself: they then time the kernel's execution alone, which is what a profiler reports for it.
+#define PROF_KERNEL(kind, expr)                                                                \
+    do {                                                                                       \
+        spd_model::Span sp_{(kind), nullptr, nullptr};                                         \
+        LaunchTiming lt_{nullptr, nullptr, false};                                             \
+        if (m->prof_on) {                                                                      \
+            sp_.a = m->take_event(); sp_.b = m->take_event();                                  \
+            if (!sp_.a || !sp_.b) return fail(SPD_ERR_HIP, "hipEventCreate failed");           \
+            lt_.start = sp_.a; lt_.stop = sp_.b;                                               \
+            launch_timing() = &lt_;                                                            \
+        }                                                                                      \
+        hipError_t pe_ = (expr);                                                               \
+        launch_timing() = nullptr;                                                             \
+        HIP_TRY(pe_);                                                                          \
+        if (m->prof_on) {                                                                      \
+            if (!lt_.used) return fail(SPD_ERR_HIP, "internal: the launch did not take its timing events"); \
+            m->spans.push_back(sp_);                                                           \
+        }                                                                                      \
+    } while (0)
+
+// a projection over one row group is a single kernel; more rows may take several passes
+#define PROF_GEMM(kind, expr)                                                                  \
+    do {                                                                                       \
+        if (rows <= kGroupRows) PROF_KERNEL(kind, expr);                                       \
+        else PROF_TRY(kind, expr);                                                             \
+    } while (0)
 }  // namespace
+
+namespace spd {
+LaunchTiming *&launch_timing() {
+    static thread_local LaunchTiming *t = nullptr;
+    return t;
+}
+}  // namespace spd
 
 extern "C" {
 
@@ -457,12 +493,12 @@ int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const flo
             qa.at = at;
             qa.head_count = (unsigned *)(m->ws + L.qa_count); qa.count_before = m->qa_count;
             qa.abort_flag = (int *)(m->ws + L.qa_abort);
-            PROF_TRY(PK_QKV, launch_qkv_attention(qa, st));
+            PROF_KERNEL(PK_QKV, launch_qkv_attention(qa, st));
             m->qa_count += (unsigned)(c.head_dim / 16);
         } else {
             g.W = m->packed + L.wqkv[l]; g.X = xn; g.N = 3 * HD; g.K = d; g.rows = rows; g.Y = qkv; g.ldy = 3 * HD;
             g.ssq_in = ssq_b; g.ssq_in_parts = (l == 0) ? 1 : d_tiles; g.eps = c.rms_eps;
-            PROF_TRY(PK_QKV, launch_gemm(g, EPI_STORE, m->t_qkv, st));
+            PROF_GEMM(PK_QKV, launch_gemm(g, EPI_STORE, m->t_qkv, st));
             for (int m0 = 0; m0 < M; m0 += kGroupRows) {         // at most 5 queries per sequence and launch
                 at.m0 = m0; at.Mq = std::min(kGroupRows, M - m0);
                 PROF_TRY(PK_ATTENTION, launch_attention(at, st));
@@ -471,21 +507,21 @@ int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const flo
         g = GemmArgs{};
         g.W = m->packed + L.wo[l]; g.X = xo; g.N = d; g.K = HD; g.rows = rows; g.Y = h; g.ldy = d;
         g.gain_next = gain_of(L.mlp_norm[l]); g.Xnext = xn; g.ssq_out = ssq_a;
-        PROF_TRY(PK_O, launch_gemm(g, EPI_RESIDUAL, m->t_o, st));
+        PROF_GEMM(PK_O, launch_gemm(g, EPI_RESIDUAL, m->t_o, st));
         g = GemmArgs{};
         g.W = m->packed + L.wgu[l]; g.X = xn; g.N = 2 * F; g.K = d; g.rows = rows; g.Xout = xf; g.K_out = F;
         g.ssq_in = ssq_a; g.ssq_in_parts = d_tiles; g.eps = c.rms_eps;
-        PROF_TRY(PK_GATE_UP, launch_gemm(g, EPI_SWIGLU, m->t_gu, st));
+        PROF_GEMM(PK_GATE_UP, launch_gemm(g, EPI_SWIGLU, m->t_gu, st));
         g = GemmArgs{};
         g.W = m->packed + L.wdown[l]; g.X = xf; g.N = d; g.K = F; g.rows = rows; g.Y = h; g.ldy = d;
         g.gain_next = gain_of(l + 1 < c.n_layers ? L.attn_norm[l + 1] : L.final_norm); g.Xnext = xn; g.ssq_out = ssq_b;
-        PROF_TRY(PK_DOWN, launch_gemm(g, EPI_RESIDUAL, m->t_down, st));
+        PROF_GEMM(PK_DOWN, launch_gemm(g, EPI_RESIDUAL, m->t_down, st));
     }
     if (logits_out) {
         GemmArgs g{};
         g.W = m->packed + L.lm_head; g.X = xn; g.N = V; g.K = d; g.rows = rows; g.Y = logits_out; g.ldy = V;
         g.ssq_in = ssq_b; g.ssq_in_parts = d_tiles; g.eps = c.rms_eps;
-        PROF_TRY(PK_LM_HEAD, launch_gemm(g, EPI_STORE, m->t_lm, st));
+        PROF_GEMM(PK_LM_HEAD, launch_gemm(g, EPI_STORE, m->t_lm, st));
     }
     if (m->dev_lens) HIP_TRY(launch_lens_add((int32_t *)(m->ws + L.d_lens) + seq0, n_seqs, M, st));
     for (int s = 0; s < n_seqs; ++s) m->lens[seq0 + s] = std::min(m->lens[seq0 + s] + M, c.max_positions);

@@ -134,7 +134,7 @@ hipError_t launch_qkv_attention(const QkvAttnArgs &a, hipStream_t stream) {
     if (a.K != 32 * kQaGemmWaves * kQaNB || t.dh != 128 || a.rows < 1 || a.rows > kGroupRows || t.n_seqs != 1 || t.M != a.rows ||
         t.m0 != 0 || t.Mq != t.M || (t.v_stride % 32) != 0 || t.v_stride < t.max_positions || t.M > t.max_positions)
         return hipErrorInvalidValue;
-    hipLaunchKernelGGL((qkv_attention_kernel<128>), dim3(t.H * (t.dh / 16)), dim3(kAttnWaves * 64), 0, stream, a);
+    launch_kernel(qkv_attention_kernel<128>, dim3(t.H * (t.dh / 16)), dim3(kAttnWaves * 64), stream, a);
     return hipGetLastError();
 }
 
