@@ -248,8 +248,8 @@ int32_t spd_device_status(spd_model *model, void *stream);
  * objects only: no device memory): a group that is a single kernel gets them as the
  * launch's own start / stop events (the kernel's execution time, as a profiler
  * reports it), a group of several launches is bracketed by events recorded on the
- * caller's stream.  With fused QKV + attention (kind 0 then covers both and kind 5
- * stays empty).  spd_trace_read WAITS for
+ * caller's stream.  Where QKV projection and attention run as one kernel, kind 0
+ * covers both and kind 5 stays empty.  spd_trace_read WAITS for
  * the recorded events (the one call here that blocks the host), adds the elapsed
  * milliseconds and launch counts per kind into h_ms_sum[n_kinds] / h_count[n_kinds] and
  * forgets them.  Kinds: 0 QKV projection, 1 O projection, 2 gate|up projection + SwiGLU,
