@@ -65,6 +65,11 @@ hipError_t launch_pack_weight(const void *src0, const void *src1, const void *sr
     return hipGetLastError();
 }
 
+LaunchTiming *&launch_timing() {
+    static thread_local LaunchTiming *t = nullptr;
+    return t;
+}
+
 // ---------------------------------------------------------------------------------
 // GEMM
 // ---------------------------------------------------------------------------------

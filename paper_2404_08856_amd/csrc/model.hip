@@ -232,12 +232,7 @@ enum ProfKind { PK_QKV = 0, PK_O, PK_GATE_UP, PK_DOWN, PK_LM_HEAD, PK_ATTENTION,
     } while (0)
 }  // namespace
 
-namespace spd {
-LaunchTiming *&launch_timing() {
-    static thread_local LaunchTiming *t = nullptr;
-    return t;
-}
-}  // namespace spd
+
 
 extern "C" {
 
