@@ -298,6 +298,24 @@ def block_loop(args, spd, synth, torch, n_seqs=1, n_prefix=None, graph_too=True,
     torch.cuda.synchronize()
     ar_ms = e0.elapsed_time(e1) / n_blocks
     res["autoregressive"] = {"ms_per_step": ar_ms, "tokens_per_s": B * 1e3 / ar_ms}
+    # the draft's own step time on the same batch, for the relative latency c of the paper's memory-bound
+    # speed-up tau / (c gamma + 1) (Section 4, metrics; c there is a ratio of parameter counts, here of measured times)
+    n_d = max(n_text - 1, 1)
+    dtok = torch.ones((B,), dtype=torch.int32, device="cuda")
+    for rep in range(n_blocks + 3):
+        if rep == 3:
+            torch.cuda.synchronize()
+            e0.record()
+        draft.spd_kv_set_len([n_d] * B)
+        for j in range(g):
+            draft.spd_draft_step(dtok.view(B, 1), 1.0, u1, Drow, dtok)
+    e1.record()
+    torch.cuda.synchronize()
+    d_ms = e0.elapsed_time(e1) / (n_blocks * g)
+    c = d_ms / ar_ms
+    tau = res["eager"]["tokens_per_block"] / B
+    res["relative_latency"] = {"draft_ms_per_step": d_ms, "c_measured": c, "c_parameter_ratio": ds.n_params() / ts.n_params(),
+                               "block_efficiency_measured": tau, "tau_over_c_gamma_plus_1": tau / (c * g + 1.0)}
     blk = res["eager"]["ms_per_block"]
     res["speedup_over_autoregressive"] = {
         "measured_random_pair": res["eager"]["tokens_per_s"] / res["autoregressive"]["tokens_per_s"],
