@@ -184,6 +184,7 @@ def side_configs(args, spd, synth, torch):
         abytes = n_seqs * (2 * args.gamma + 1) * V * 4
         per_sigma[str(sigma)] = {"us": us, "GBps": abytes / (us * 1e-6) / 1e9, "mean_accepted": float(k.float().mean())}
     res["block_loop"] = block_loop(args, spd, synth, torch)
+    res["block_loop_paper_draft_shape"] = block_loop(args, spd, synth, torch, graph_too=False, draft_name="draft_paper_115m")
     res["block_loop_batch8_ctx2048"] = block_loop(args, spd, synth, torch, n_seqs=8, n_prefix=2048, graph_too=False, projected=True)
     res["batched_verify"] = batched_verify(args, spd, synth, torch)
     res["accept_kernel"] = {"workload": f"{n_seqs} sequences x (gamma+1={args.gamma + 1}) rows x vocab {V}, logit inputs, temperature 1; "
@@ -193,13 +194,13 @@ def side_configs(args, spd, synth, torch):
     return res
 
 
-def block_loop(args, spd, synth, torch, n_seqs=1, n_prefix=None, graph_too=True, projected=False):
+def block_loop(args, spd, synth, torch, n_seqs=1, n_prefix=None, graph_too=True, projected=False, draft_name="draft_110m"):
     """Whole speculative-decoding blocks (gamma draft steps of the ~110M draft, one 7B target call, accept,
     commit) with lengths and tokens on the device: back-to-back launches, and one block captured in a graph.
     For n_seqs > 1 or a long prefix only sequence lengths are set (zero-filled caches): timing only."""
     M = args.gamma + 1
     B = n_seqs
-    ts, ds = synth.SHAPES["llama7b"], synth.SHAPES["draft_110m"]
+    ts, ds = synth.SHAPES["llama7b"], synth.SHAPES[draft_name]
     real_prefill = n_prefix is None and B == 1
     if n_prefix is None:
         n_prefix = args.image_rows + args.text_tokens
@@ -246,7 +247,7 @@ def block_loop(args, spd, synth, torch, n_seqs=1, n_prefix=None, graph_too=True,
         spd.spd_block_finish(target, draft, logits, D, vt, ua, 1.0, k, y, din, out, n_out, ws)
 
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    res = {"workload": f"7B target (prefix {n_prefix}) + draft_110m, gamma={g}, batch {B}, temperature 1, random target weights, "
+    res = {"workload": f"7B target (prefix {n_prefix}) + {draft_name}, gamma={g}, batch {B}, temperature 1, random target weights, "
                        + ("draft = the target's first 12 layers projected to d=768 by fixed random orthogonal maps"
                           if projected else "independent random draft")
                        + " (acceptance is whatever such a pair gives; it is measured, not designed)"
