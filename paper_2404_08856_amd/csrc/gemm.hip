@@ -102,6 +102,9 @@ struct GemmKernelArgs {
     int KS_out;
 };
 
+// General one-row-group kernel (any K; used where the register-resident variant below does not
+// apply, e.g. the down projection with K = 11008).  The NG parameter is kept at 1: several row
+// groups go through gemm_multi_kernel.
 // Persistent workgroups: workgroup b owns tiles b, b + gridDim.x, ...; its WAVES waves split
 // the K range of every tile.  Each wave keeps a ring of U weight blocks (and the matching
 // activation blocks) in flight: right after a block has been consumed by the matrix core its
