@@ -79,7 +79,7 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
     const size_t HD = (size_t)H * DH;
     const int VS = a.v_stride;                    // positions per row of the transposed V cache
     uint16_t *Kc = (uint16_t *)a.k_cache + pair * a.max_positions * DH;        // [pos][DH]
-    uint16_t *Vt = (uint16_t *)a.v_cache + pair * (size_t)DH * VS;             // [DH][VS]
+    uint16_t *Vt = (uint16_t *)a.v_cache + pair * (size_t)DH * VS;             // [VS / 32][DH][32]: see launch.h
 
     __shared__ float qf[8][DH];
     __shared__ float kf[8][DH];
@@ -110,7 +110,7 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
                 }
 #pragma unroll
                 for (int i = 0; i < NDT; ++i)
-                    vreg[s][i] = *reinterpret_cast<const uint4 *>(Vt + (size_t)(dim0 + 16 * i + r) * VS + 32 * unit + 8 * g);
+                    vreg[s][i] = *reinterpret_cast<const uint4 *>(Vt + ((size_t)unit * DH + dim0 + 16 * i + r) * 32 + 8 * g);
             }
         }
     };
@@ -143,8 +143,8 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
                 if (ds == 0) {                                         // one workgroup of the head appends
                     Kc[(size_t)pos * DH + j] = kb1;
                     Kc[(size_t)pos * DH + j + HALF] = kb2;
-                    Vt[(size_t)j * VS + pos] = vb1;
-                    Vt[(size_t)(j + HALF) * VS + pos] = vb2;
+                    Vt[((size_t)(pos >> 5) * DH + j) * 32 + (pos & 31)] = vb1;
+                    Vt[((size_t)(pos >> 5) * DH + j + HALF) * 32 + (pos & 31)] = vb2;
                 }
             } else {
                 kf[i][j] = 0.f; kf[i][j + HALF] = 0.f;

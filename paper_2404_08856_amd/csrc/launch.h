@@ -91,7 +91,8 @@ struct AttnArgs {
     const float *qkv;        // [rows, 3 * H * dh] (q | k | v), before RoPE
     const float *rope;       // [max_positions, dh / 2, 2] (cos, sin)
     void *k_cache;           // this layer: bf16 [max_seqs, H, max_positions, dh]   (K after RoPE)
-    void *v_cache;           // this layer: bf16 [max_seqs, H, dh, v_stride]        (V transposed)
+    void *v_cache;           // this layer: bf16 [max_seqs, H, v_stride / 32, dh, 32]: V transposed in blocks of 32
+                             // positions, so that the dh x 32 tile one unit of 32 keys needs is 64 * dh contiguous bytes
     void *xout;              // packed activations, K = H * dh (attention output)
     int n_seqs, M, H, dh, max_positions, v_stride;
     int m0, Mq;              // this launch handles rows m0 .. m0 + Mq - 1 of every sequence (Mq <= 5); rows

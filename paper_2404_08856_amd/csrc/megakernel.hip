@@ -343,7 +343,7 @@ __device__ __forceinline__ void attention_item(const MegaAttn &a, int ds, int hh
                 }
 #pragma unroll
                 for (int i = 0; i < NDT; ++i)
-                    vreg[s][i] = *reinterpret_cast<const uint4 *>(Vt + (size_t)(dim0 + 16 * i + r) * VS + 32 * unit + 8 * g);
+                    vreg[s][i] = *reinterpret_cast<const uint4 *>(Vt + ((size_t)unit * DH + dim0 + 16 * i + r) * 32 + 8 * g);
             }
         }
     };
@@ -375,8 +375,8 @@ __device__ __forceinline__ void attention_item(const MegaAttn &a, int ds, int hh
                 if (ds == 0) {
                     Kc[(size_t)pos * DH + j] = kb1;
                     Kc[(size_t)pos * DH + j + HALF] = kb2;
-                    Vt[(size_t)j * VS + pos] = vb1;
-                    Vt[(size_t)(j + HALF) * VS + pos] = vb2;
+                    Vt[((size_t)(pos >> 5) * DH + j) * 32 + (pos & 31)] = vb1;
+                    Vt[((size_t)(pos >> 5) * DH + j + HALF) * 32 + (pos & 31)] = vb2;
                 }
             } else {
                 kf[i][j] = 0.f; kf[i][j + HALF] = 0.f;
