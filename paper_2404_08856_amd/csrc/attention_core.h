@@ -173,7 +173,6 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
 
     // ---- cached keys on the matrix cores ----------------------------------------------------
     float m_run = -INFINITY, l_run = 0.f;         // of query r % 5 (replicated over lane groups and terms)
-    const int qsrc = (lane & 48) + (r % kGroupRows);                   // lane holding term 0 of this lane's query
     const float sel0 = r < 5 ? 1.f : 0.f, sel1 = (r >= 5 && r < 10) ? 1.f : 0.f, sel2 = (r >= 10 && r < 15) ? 1.f : 0.f;
     f32x4_t acc_o[NDT];
 #pragma unroll
@@ -199,8 +198,8 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
                 for (int c = 0; c < NC; ++c) acc = mfma16(kreg[s][ab][c], qreg[c], acc);
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    float x = acc[v];                                  // the three term columns of this lane's query
-                    x = __shfl(x, qsrc) + __shfl(x, qsrc + kGroupRows) + __shfl(x, qsrc + 2 * kGroupRows);
+                    float x = acc[v];                                  // summed over the three term columns of this lane's query
+                    x = sum_terms_all(x, r);
                     const int key = 32 * unit + 8 * g + 4 * ab + v;    // D row 4g + v of tile ab
                     x = key < P ? x : -INFINITY;
                     sv[ab][v] = x;

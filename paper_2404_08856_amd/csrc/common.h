@@ -50,10 +50,26 @@ __device__ __forceinline__ void split3(float x, uint16_t (&t)[kTerms]) {
     t[1] = f32_to_bf16_bits(r1);
     t[2] = f32_to_bf16_bits(r1 - bf16_bits_to_f32(t[1]));
 }
+// Data-parallel-primitive moves inside a row of 16 lanes (no LDS traffic, no wait): lane i of a row
+// receives the value of lane i + n (row_shl) or i - n (row_shr) of the same row, 0 beyond the row
+// (lane semantics checked on the device).
+template <int CTRL>
+__device__ __forceinline__ float dpp_row(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+constexpr int kRowShl = 0x100, kRowShr = 0x110;
+
 // Sum of the three term columns of an accumulator tile: on lanes with lane % 16 < 5 the result
-// is D[.][c] + D[.][c + 5] + D[.][c + 10]; other lanes hold garbage.
+// is D[.][c] + D[.][c + 5] + D[.][c + 10]; other lanes hold garbage (finite if the tile is).
 __device__ __forceinline__ float sum_terms(float x) {
-    return x + __shfl_down(x, kGroupRows) + __shfl_down(x, 2 * kGroupRows);
+    return x + dpp_row<kRowShl + kGroupRows>(x) + dpp_row<kRowShl + 2 * kGroupRows>(x);
+}
+// The same sum on every lane of the three term columns: lane r < 15 of a row gets the sum of
+// row r % 5; lane 15 gets a finite value nobody uses.
+__device__ __forceinline__ float sum_terms_all(float x, int r) {
+    const float y = sum_terms(x);
+    const float y5 = dpp_row<kRowShr + kGroupRows>(y), y10 = dpp_row<kRowShr + 2 * kGroupRows>(y);
+    return r < kGroupRows ? y : (r < 2 * kGroupRows ? y5 : y10);
 }
 
 // ---------------------------------------------------------------------------------

@@ -403,7 +403,6 @@ __device__ __forceinline__ void attention_item(const MegaAttn &a, int ds, int hh
     __syncthreads();
 
     float m_run = -INFINITY, l_run = 0.f;         // of query r % 5
-    const int qsrc = (lane & 48) + (r % kGroupRows);
     fx4 acc_o[NDT];
 #pragma unroll
     for (int i = 0; i < NDT; ++i) acc_o[i] = fx4{0.f, 0.f, 0.f, 0.f};
@@ -428,7 +427,7 @@ __device__ __forceinline__ void attention_item(const MegaAttn &a, int ds, int hh
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     float x = acc[v];
-                    x = __shfl(x, qsrc) + __shfl(x, qsrc + kGroupRows) + __shfl(x, qsrc + 2 * kGroupRows);
+                    x = sum_terms_all(x, r);
                     const int key = 32 * unit + 8 * g + 4 * ab + v;
                     x = (unit < u_end && key < P) ? x : -INFINITY;
                     sv[s][ab][v] = x;
