@@ -297,9 +297,10 @@ def test_batched_verify_many_row_groups(n_seqs, M):
     model.close()
 
 
+@pytest.mark.parametrize("dev_lens", [False, True])
 @pytest.mark.parametrize("fuse", [True, False])
 @pytest.mark.parametrize("M", [1, 5])
-def test_qkv_attention_fused_and_separate_kernels(fuse, M, monkeypatch):
+def test_qkv_attention_fused_and_separate_kernels(fuse, M, dev_lens, monkeypatch):
     """d_model 4096 with 2 heads of 128: the shape class that takes the fused QKV + attention kernel
     (one workgroup per head and 16 output dimensions, per-head arrival counter), against the
     oracle, with the fusion on and off; several calls so that the counters advance."""
@@ -316,6 +317,8 @@ def test_qkv_attention_fused_and_separate_kernels(fuse, M, monkeypatch):
     last = torch.empty(shape.vocab, dtype=torch.float32, device="cuda")
     model.spd_prefill_tokens(0, torch.from_numpy(toks).cuda(), last)
     check_logits(last.cpu().numpy(), ref_last, "prefill")
+    if dev_lens:                                            # KV lengths read from device memory by the kernels
+        model.spd_kv_lens_to_device()
     for step in range(3):
         vt = synth.text_tokens(M, shape.vocab, 60 + step)
         ref = dec.forward_tokens(cfg, wn, cache, vt)
@@ -323,6 +326,9 @@ def test_qkv_attention_fused_and_separate_kernels(fuse, M, monkeypatch):
         model.spd_verify_forward(torch.from_numpy(vt).cuda()[None].contiguous(), out)
         check_logits(out.cpu().numpy()[0], ref, f"step {step}")
     model.spd_device_status()
+    if dev_lens:
+        model.spd_kv_lens_from_device()
+    assert model.spd_kv_get_len(1) == [cache.length]
     model.close()
 
 
