@@ -24,6 +24,7 @@ __global__ __launch_bounds__(256) void input_rows_kernel(const uint16_t *__restr
     const float *src_row = embeds ? embeds + (size_t)row * d : nullptr;
     float *dst = h + (size_t)row * d;
     float ss = 0.f;
+#pragma unroll 4
     for (int k = threadIdx.x * 4; k < d; k += 256 * 4) {              // d % 32 == 0
         float4 v;
         if (src_tok) {
