@@ -487,3 +487,33 @@ def test_tracing_counts_every_launch_group():
     model.spd_verify_forward(vt, out)
     assert all(n == 0 for ms, n in model.spd_trace_read().values())
     model.close()
+
+
+@pytest.mark.parametrize("shape_name,prefix", [("tiny_draft", 2000), ("tiny_target", 1537), ("tiny_draft", 769)])
+def test_long_context_needs_several_key_iterations_per_wave(shape_name, prefix):
+    """Contexts beyond 768 keys: every wave of the attention kernel walks its keys in more than one
+    iteration (the shorter cases above finish in one)."""
+    run_case(synth.SHAPES[shape_name], 0, prefix, 5, seed=prefix % 97, extra_steps=1)
+
+
+def test_long_context_batch_with_unsliced_heads(monkeypatch):
+    """Head dimension 128, several sequences at contexts of 900 to 1300 keys, every head slicing."""
+    shape = synth.ModelShape(1, 4096, 2, 128, 256, 1024)
+    model, wn = build_pair(shape, 83, 3, 1320)
+    cfg = oracle_cfg(shape)
+    caches = []
+    for s in range(3):
+        toks = synth.text_tokens(900 + 200 * s, shape.vocab, 900 + s)
+        c = dec.KVCache(cfg, 1320)
+        dec.forward_tokens(cfg, wn, c, toks)
+        caches.append(c)
+        model.spd_prefill_tokens(s, torch.from_numpy(toks).cuda())
+    for slices in (1, 2, 8):
+        monkeypatch.setenv("SPD_ATTN_SLICES", str(slices))
+        vt = np.stack([synth.text_tokens(4, shape.vocab, 950 + 10 * slices + s) for s in range(3)])
+        out = torch.empty((3, 4, shape.vocab), dtype=torch.float32, device="cuda")
+        model.spd_verify_forward(torch.from_numpy(vt).cuda(), out)
+        got = out.cpu().numpy()
+        for s in range(3):
+            check_logits(got[s], dec.forward_tokens(cfg, wn, caches[s], vt[s]), f"slices {slices} seq {s}")
+    model.close()
