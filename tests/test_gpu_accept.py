@@ -117,7 +117,7 @@ def test_accept_greedy_logits():
     assert 0 < k.sum() < n_seqs * gamma            # both branches exercised
 
 
-@pytest.mark.parametrize("V,gamma,n_seqs", [(16, 1, 1), (1000, 2, 3), (1024, 7, 5), (32000, 1, 2), (50, 63, 1)])
+@pytest.mark.parametrize("V,gamma,n_seqs", [(16, 1, 1), (1000, 2, 3), (1024, 7, 5), (32000, 1, 2), (50, 63, 1), (40000, 2, 2), (32768, 1, 1), (1002, 3, 2)])
 def test_accept_shapes_and_edges_bit_exact(V, gamma, n_seqs):
     spd = spd_mod()
     lt, ld = synth.accept_workload(n_seqs, gamma, V, 1.0, seed=V + gamma)
