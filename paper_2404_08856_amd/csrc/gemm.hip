@@ -407,74 +407,97 @@ static hipError_t launch_multi(const GemmKernelArgs &k, int epilogue, int grid, 
 // of its register slot with the block U steps ahead (same tile, or the workgroup's next
 // tile), so all of a wave's loads for the next tile are in flight while the tile is
 // reduced across waves and written out.
-template <int WAVES, int EPI, int NB, int U>
-__global__ __launch_bounds__(WAVES * 64, (NB <= 8 ? 4 : 2)) void gemm_regb_kernel(GemmKernelArgs a) {
+// NG = 2: rows 6..10 (two row groups) with both groups' activation slices resident: every weight block
+// feeds two matrix-core steps; the epilogue duty of a tile goes to four waves (a pair per group).
+template <int WAVES, int EPI, int NB, int U, int NG = 1>
+__global__ __launch_bounds__(WAVES * 64, (NG > 1 ? 1 : (NB <= 8 ? 4 : 2))) void gemm_regb_kernel(GemmKernelArgs a) {
     static_assert(NB % U == 0, "ring must divide the per-wave K range");
+    static_assert(2 * NG <= WAVES && WAVES % (2 * NG) == 0, "a pair of epilogue waves per row group");
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int KS = a.KS;                                  // == WAVES * NB
     const int s0 = w * NB;
     const int G = gridDim.x;
 
-    __shared__ float red[2][WAVES][16][8];
+    __shared__ float red[2][WAVES][NG][16][8];
 
     int t = blockIdx.x;
     if (t >= a.n_tiles) return;
 
-    uint4 av[U], bv[NB];
+    uint4 av[U], bv[NG][NB];
 #pragma unroll
     for (int u = 0; u < U; ++u) av[u] = load_stream(a.W + ((size_t)t * KS + s0 + u) * 64 + lane);
 #pragma unroll
-    for (int i = 0; i < NB; ++i) bv[i] = a.X[(size_t)(s0 + i) * 64 + lane];
-
-    // Epilogue role of this thread: pairs of waves take turns (tile k is finished by waves
-    // 2 (k mod WAVES/2) and +1); a thread always handles output row em and column en.
-    const int en = lane & 15, em = (w & 1) * 4 + (lane >> 4);
-    const bool row_ok = em < a.rows;
-    float inv_row = 1.0f;
-    if (a.ssq_in) {                                       // 1 / rms of row em from the per-tile partial sums
-        // the row's partials are contiguous: 16 lanes read them as float4, all loads in flight at once
-        float sum = 0.f;
-        if (row_ok) {
-            const float *part = a.ssq_in + (size_t)em * (KS * 2);
-            if ((a.ssq_in_parts & 3) == 0) {
-#pragma unroll 4
-                for (int p = en; p < (a.ssq_in_parts >> 2); p += 16) {
-                    const float4 q = reinterpret_cast<const float4 *>(part)[p];
-                    sum += (q.x + q.y) + (q.z + q.w);
-                }
-            } else {
-                for (int p = en; p < a.ssq_in_parts; p += 16) sum += part[p];
-            }
-        }
+    for (int g = 0; g < NG; ++g)
 #pragma unroll
-        for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-        inv_row = 1.0f / sqrtf(sum * a.inv_d + a.eps);
+        for (int i = 0; i < NB; ++i) bv[g][i] = a.X[((size_t)g * KS + s0 + i) * 64 + lane];
+
+    // Epilogue role of this thread: 2 NG consecutive waves take a tile (tile k starts at wave
+    // 2 NG (k mod WAVES / (2 NG))), a pair per row group; a thread always handles row slot em
+    // and column en, of the group its pair has in that tile.
+    const int en = lane & 15, em = (w & 1) * 4 + (lane >> 4);
+    float inv_row[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) inv_row[g] = 1.0f;
+    if (a.ssq_in) {                                       // 1 / rms of rows em and 5 + em from the per-tile partial sums
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int row = g * kGroupRows + em;
+            // the row's partials are contiguous: 16 lanes read them as float4, all loads in flight at once
+            float sum = 0.f;
+            if (em < kGroupRows && row < a.rows) {
+                const float *part = a.ssq_in + (size_t)row * (KS * 2);
+                if ((a.ssq_in_parts & 3) == 0) {
+#pragma unroll 4
+                    for (int p = en; p < (a.ssq_in_parts >> 2); p += 16) {
+                        const float4 q = reinterpret_cast<const float4 *>(part)[p];
+                        sum += (q.x + q.y) + (q.z + q.w);
+                    }
+                } else {
+                    for (int p = en; p < a.ssq_in_parts; p += 16) sum += part[p];
+                }
+            }
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+            inv_row[g] = 1.0f / sqrtf(sum * a.inv_d + a.eps);
+        }
     }
 
     int parity = 0, turn = 0;
-    for (; t < a.n_tiles; t += G, parity ^= 1, turn = (turn + 2) % WAVES) {
+    for (; t < a.n_tiles; t += G, parity ^= 1, turn = (turn + 2 * NG) % WAVES) {
         const int tn = t + G;
         const bool has_next = tn < a.n_tiles;
-        const bool my_turn = (w == turn) || (w == turn + 1);
+        const int rel = w - turn;                         // 0 .. 2 NG - 1 for the waves on duty
+        const bool my_turn = rel >= 0 && rel < 2 * NG;
+        const int eg = my_turn ? (rel >> 1) : 0;          // row group of this wave's pair
+        const int erow = eg * kGroupRows + em;
+        const bool row_ok = em < kGroupRows && erow < a.rows;
         const bool e_active = my_turn && row_ok && (EPI != EPI_SWIGLU || en < 8);
+        float inv = inv_row[0];
+#pragma unroll
+        for (int g = 1; g < NG; ++g) inv = (eg == g) ? inv_row[g] : inv;
         float hold = 0.f;
-        if (EPI == EPI_RESIDUAL && e_active) hold = a.Y[(size_t)em * a.ldy + (size_t)t * 16 + en];
+        if (EPI == EPI_RESIDUAL && e_active) hold = a.Y[(size_t)erow * a.ldy + (size_t)t * 16 + en];
 
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        f32x4_t acc[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) acc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         const uint4 *wnext = has_next ? a.W + ((size_t)tn * KS + s0) * 64 : a.X;   // past the end: harmless re-read
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            acc = mfma_bf16(av[i % U], bv[i], acc);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[g] = mfma_bf16(av[i % U], bv[g][i], acc[g]);
             if (i + U < NB) av[i % U] = load_stream(a.W + ((size_t)t * KS + s0 + i + U) * 64 + lane);
             else av[i % U] = load_stream(wnext + (size_t)(has_next ? (i + U - NB) : 0) * 64 + lane);
             __builtin_amdgcn_sched_barrier(0);            // keep "consume slot, refill slot" in program order
         }
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const float x = sum_terms(acc[v]);
-            if ((lane & 15) < kGroupRows) red[parity][w][4 * (lane >> 4) + v][lane & 15] = x;
-        }
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float x = sum_terms(acc[g][v]);
+                if ((lane & 15) < kGroupRows) red[parity][w][g][4 * (lane >> 4) + v][lane & 15] = x;
+            }
         __syncthreads();
         if (!my_turn) continue;
 
@@ -483,59 +506,59 @@ __global__ __launch_bounds__(WAVES * 64, (NB <= 8 ? 4 : 2)) void gemm_regb_kerne
                 float gate = 0.f, up = 0.f;
 #pragma unroll
                 for (int ww = 0; ww < WAVES; ++ww) {
-                    gate += red[parity][ww][en][em];
-                    up += red[parity][ww][en + 8][em];
+                    gate += red[parity][ww][eg][en][em];
+                    up += red[parity][ww][eg][en + 8][em];
                 }
-                gate *= inv_row;
-                up *= inv_row;
+                gate *= inv;
+                up *= inv;
                 float val = gate / (1.0f + expf(-gate)) * up;
                 int f = t * 8 + en;
                 uint16_t t3[kTerms];
                 split3(val, t3);
 #pragma unroll
-                for (int q = 0; q < kTerms; ++q) a.Xout[xpack_index(em, f, a.KS_out, q)] = t3[q];
+                for (int q = 0; q < kTerms; ++q) a.Xout[xpack_index(erow, f, a.KS_out, q)] = t3[q];
             }
         } else {
             float sum = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < WAVES; ++ww) sum += red[parity][ww][en][em];
-            sum *= inv_row;
+            for (int ww = 0; ww < WAVES; ++ww) sum += red[parity][ww][eg][en][em];
+            sum *= inv;
             const int col = t * 16 + en;
             if (EPI == EPI_STORE) {
-                if (e_active) a.Y[(size_t)em * a.ldy + col] = sum;
+                if (e_active) a.Y[(size_t)erow * a.ldy + col] = sum;
             } else {
                 float hnew = e_active ? hold + sum : 0.f;
                 if (e_active) {
-                    a.Y[(size_t)em * a.ldy + col] = hnew;
+                    a.Y[(size_t)erow * a.ldy + col] = hnew;
                     if (a.gain_next) {
                         uint16_t t3[kTerms];
                         split3(hnew * a.gain_next[col], t3);
                         const int KSn = a.n_tiles / 2;
 #pragma unroll
-                        for (int q = 0; q < kTerms; ++q) a.Xnext[xpack_index(em, col, KSn, q)] = t3[q];
+                        for (int q = 0; q < kTerms; ++q) a.Xnext[xpack_index(erow, col, KSn, q)] = t3[q];
                     }
                 }
                 float sq = hnew * hnew;
 #pragma unroll
                 for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
-                if (a.ssq_out && en == 0 && e_active) a.ssq_out[(size_t)em * a.n_tiles + t] = sq;
+                if (a.ssq_out && en == 0 && e_active) a.ssq_out[(size_t)erow * a.n_tiles + t] = sq;
             }
         }
     }
 }
 
-template <int WAVES, int NB, int U>
+template <int WAVES, int NB, int U, int NG = 1>
 static hipError_t launch_regb(const GemmKernelArgs &k, int epilogue, int grid, hipStream_t stream) {
     dim3 g(grid), block(WAVES * 64);
     switch (epilogue) {
         case EPI_STORE:
-            launch_kernel(gemm_regb_kernel<WAVES, EPI_STORE, NB, U>, g, block, stream, k);
+            launch_kernel(gemm_regb_kernel<WAVES, EPI_STORE, NB, U, NG>, g, block, stream, k);
             break;
         case EPI_RESIDUAL:
-            launch_kernel(gemm_regb_kernel<WAVES, EPI_RESIDUAL, NB, U>, g, block, stream, k);
+            launch_kernel(gemm_regb_kernel<WAVES, EPI_RESIDUAL, NB, U, NG>, g, block, stream, k);
             break;
         case EPI_SWIGLU:
-            launch_kernel(gemm_regb_kernel<WAVES, EPI_SWIGLU, NB, U>, g, block, stream, k);
+            launch_kernel(gemm_regb_kernel<WAVES, EPI_SWIGLU, NB, U, NG>, g, block, stream, k);
             break;
         default:
             return hipErrorInvalidValue;
@@ -607,6 +630,11 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStre
         if (waves == 8 && k.KS == 8 * 8) return launch_regb<8, 8, 8>(k, epilogue, grid_for(2), stream);
         if (waves == 4 && k.KS == 4 * 8) return launch_regb<4, 8, 8>(k, epilogue, grid_for(4), stream);
         if (waves == 4 && k.KS == 4 * 16) return launch_regb<4, 16, 8>(k, epilogue, grid_for(2), stream);
+    }
+    if (groups == 2 && !tune.no_regb) {                 // rows 6..10: both activation slices register-resident
+        const int g1 = pick_grid(k.n_tiles, tune.grid_cap > 0 ? tune.grid_cap : 256);
+        if (waves == 16 && k.KS == 16 * 8) return launch_regb<16, 8, 8, 2>(k, epilogue, g1, stream);
+        if (k.KS == 8 * 16) return launch_regb<8, 16, 8, 2>(k, epilogue, g1, stream);
     }
 #define SPD_GEMM_CASE(NG_, W_, U_) return launch_epi<NG_, W_, U_>(k, epilogue, grid, stream)
     if (groups == 1) {

@@ -412,7 +412,7 @@ def test_image_aware_draft_takes_embedding_rows():
     model.close()
 
 
-@pytest.mark.parametrize("n_seqs,M", [(2, 4), (3, 7), (8, 8)])
+@pytest.mark.parametrize("n_seqs,M", [(2, 4), (3, 7), (8, 8), (1, 6), (1, 8), (2, 5)])
 def test_batched_verify_wide_model(n_seqs, M):
     """Several row groups on a model whose matrices have 256 and more tiles (d_model 4096): the
     multi-group projection kernel with one and with three tiles in flight, all three epilogues."""
