@@ -1,7 +1,9 @@
-// RoPE + KV-cache append + causal attention of up to 5 new queries per sequence and launch over
-// the cached prefix (image rows + text + already accepted tokens), on the matrix cores.  A call
-// with 6..8 rows per sequence takes two launches: the second sees the first one's rows in the
-// cache like any other prefix position.
+// RoPE + KV-cache append + causal attention of up to 8 new queries per sequence and launch over
+// the cached prefix (image rows + text + already accepted tokens), on the matrix cores.  The
+// queries form groups of 5 (three bf16 terms each fill 15 of the 16 operand columns); 6..8
+// queries are two groups multiplied with the same cached keys.  Longer runs of new rows (the
+// prefill) take several launches: a later one sees the earlier ones' rows in the cache like any
+// other prefix position.
 //
 // One workgroup (12 waves) per (sequence, head, slice of 16 or more output dimensions).  The cached keys are cut
 // into units of 32; every wave owns a contiguous run of units and walks it 2 units (64 keys)
@@ -57,7 +59,9 @@ __device__ __forceinline__ uint32_t pack2(uint16_t lo, uint16_t hi) { return (ui
 // are read with device-scope loads.
 // `rows_ready()` is called by every thread after the loads of the cached keys have been issued and
 // before the new rows are read: the place to wait for their producer.
-template <int DH, int DS, int AW, int UPI, bool DEV, class ReadyFn>
+// QG: query groups of 5 handled by one launch (1: up to 5 new rows per sequence, 2: up to 8; the
+// cached keys are then multiplied with both groups from the same registers).
+template <int DH, int DS, int AW, int UPI, bool DEV, int QG, class ReadyFn>
 __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, const int ds, const int seq, ReadyFn rows_ready) {
     constexpr int HALF = DH / 2;
     constexpr int NC = DH / 32;                   // 32-dim chunks of a key row
@@ -84,7 +88,7 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
     __shared__ float qf[8][DH];
     __shared__ float kf[8][DH];
     __shared__ float vf[8][DH];
-    __shared__ uint16_t qb[NC][64][8];            // q as matrix-core B operand (three bf16 terms)
+    __shared__ uint16_t qb[QG][NC][64][8];        // q as matrix-core B operand (three bf16 terms), per query group
     __shared__ float pn[8][8];
     __shared__ float part_m[AW + 1][8];
     __shared__ float part_l[AW + 1][8];
@@ -120,7 +124,7 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
     // ---- RoPE on q, k of the new rows; bf16 rounding of new k, v; cache append ------------
     {
         const float scale = 1.0f / sqrtf((float)DH);
-        for (int idx = tid; idx < 8 * HALF; idx += AW * 64) {
+        for (int idx = tid; idx < (QG == 1 ? 8 : 10) * HALF; idx += AW * 64) {      // rows 8, 9: zero columns of group 1
             const int i = idx / HALF, j = idx % HALF;
             float qa = 0.f, qc = 0.f;
             if (i < M) {
@@ -146,40 +150,48 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
                     Vt[((size_t)(pos >> 5) * DH + j) * 32 + (pos & 31)] = vb1;
                     Vt[((size_t)(pos >> 5) * DH + j + HALF) * 32 + (pos & 31)] = vb2;
                 }
-            } else {
+            } else if (i < 8) {
                 kf[i][j] = 0.f; kf[i][j + HALF] = 0.f;
                 vf[i][j] = 0.f; vf[i][j + HALF] = 0.f;
             }
-            qf[i][j] = qa;
-            qf[i][j + HALF] = qc;
-            // B operand: column i + 5 t holds bf16 term t of q_i (rows 5..7 of the loop carry zeros)
-            if (i < kGroupRows) {
+            if (i < 8) {
+                qf[i][j] = qa;
+                qf[i][j + HALF] = qc;
+            }
+            // B operand: column c + 5 t of group i / 5 holds bf16 term t of q_i, c = i % 5 (rows beyond M carry zeros)
+            if (i < kGroupRows * QG) {
                 uint16_t t1[kTerms], t2[kTerms];
                 split3(qa, t1);
                 split3(qc, t2);
-                const int d1 = j, d2 = j + HALF;
+                const int d1 = j, d2 = j + HALF, qg = i / kGroupRows, c5 = i % kGroupRows;
 #pragma unroll
                 for (int t = 0; t < kTerms; ++t) {
-                    qb[d1 >> 5][i + kGroupRows * t + 16 * ((d1 & 31) >> 3)][d1 & 7] = t1[t];
-                    qb[d2 >> 5][i + kGroupRows * t + 16 * ((d2 & 31) >> 3)][d2 & 7] = t2[t];
+                    qb[qg][d1 >> 5][c5 + kGroupRows * t + 16 * ((d1 & 31) >> 3)][d1 & 7] = t1[t];
+                    qb[qg][d2 >> 5][c5 + kGroupRows * t + 16 * ((d2 & 31) >> 3)][d2 & 7] = t2[t];
                 }
-            } else if (i == kGroupRows) {             // column 15 (unused): keep it finite
-                qb[j >> 5][15 + 16 * ((j & 31) >> 3)][j & 7] = 0;
-                qb[(j + HALF) >> 5][15 + 16 * (((j + HALF) & 31) >> 3)][(j + HALF) & 7] = 0;
             }
+        }
+        for (int idx = tid; idx < QG * DH; idx += AW * 64) {          // column 15 (unused): keep it finite
+            const int qg = idx / DH, dd = idx % DH;
+            qb[qg][dd >> 5][15 + 16 * ((dd & 31) >> 3)][dd & 7] = 0;
         }
     }
     __syncthreads();
 
     // ---- cached keys on the matrix cores ----------------------------------------------------
-    float m_run = -INFINITY, l_run = 0.f;         // of query r % 5 (replicated over lane groups and terms)
+    float m_run[QG], l_run[QG];                   // of query 5 qg + r % 5 (replicated over lane groups and terms)
+#pragma unroll
+    for (int qg = 0; qg < QG; ++qg) { m_run[qg] = -INFINITY; l_run[qg] = 0.f; }
     const float sel0 = r < 5 ? 1.f : 0.f, sel1 = (r >= 5 && r < 10) ? 1.f : 0.f, sel2 = (r >= 10 && r < 15) ? 1.f : 0.f;
-    f32x4_t acc_o[NDT];
+    f32x4_t acc_o[QG][NDT];
+    uint4 qreg[QG][NC];
 #pragma unroll
-    for (int i = 0; i < NDT; ++i) acc_o[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    uint4 qreg[NC];
+    for (int qg = 0; qg < QG; ++qg) {
 #pragma unroll
-    for (int c = 0; c < NC; ++c) qreg[c] = *reinterpret_cast<const uint4 *>(&qb[c][lane][0]);
+        for (int i = 0; i < NDT; ++i) acc_o[qg][i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < NC; ++c) qreg[qg][c] = *reinterpret_cast<const uint4 *>(&qb[qg][c][lane][0]);
+    }
 
     for (int u0 = u_begin; u0 < u_end; u0 += UPI) {
         if (u0 != u_begin) issue_loads(u0);
@@ -189,62 +201,69 @@ __device__ __forceinline__ void attention_core(const AttnArgs &a, const int hh, 
         for (int s = 0; s < UPI; ++s) {
             const int unit = u0 + s;
             if (unit >= u_end) break;                                  // wave-uniform
-            float sv[2][4];
-            float mx = -INFINITY;
 #pragma unroll
-            for (int ab = 0; ab < 2; ++ab) {
-                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+            for (int qg = 0; qg < QG; ++qg) {
+                float sv[2][4];
+                float mx = -INFINITY;
 #pragma unroll
-                for (int c = 0; c < NC; ++c) acc = mfma16(kreg[s][ab][c], qreg[c], acc);
+                for (int ab = 0; ab < 2; ++ab) {
+                    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    float x = acc[v];                                  // summed over the three term columns of this lane's query
-                    x = sum_terms_all(x, r);
-                    const int key = 32 * unit + 8 * g + 4 * ab + v;    // D row 4g + v of tile ab
-                    x = key < P ? x : -INFINITY;
-                    sv[ab][v] = x;
-                    mx = fmaxf(mx, x);
+                    for (int c = 0; c < NC; ++c) acc = mfma16(kreg[s][ab][c], qreg[qg][c], acc);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        float x = acc[v];                              // summed over the three term columns of this lane's query
+                        x = sum_terms_all(x, r);
+                        const int key = 32 * unit + 8 * g + 4 * ab + v;    // D row 4g + v of tile ab
+                        x = key < P ? x : -INFINITY;
+                        sv[ab][v] = x;
+                        mx = fmaxf(mx, x);
+                    }
                 }
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run, mx);                      // finite: a unit has >= 1 valid key
-            const float rescale = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);
-            float lsum = 0.f;
-            uint32_t hv[8];
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run[qg], mx);              // finite: a unit has >= 1 valid key
+                const float rescale = (m_run[qg] == -INFINITY) ? 0.f : expf(m_run[qg] - m_new);
+                float lsum = 0.f;
+                uint32_t hv[8];
 #pragma unroll
-            for (int ab = 0; ab < 2; ++ab)
+                for (int ab = 0; ab < 2; ++ab)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float p = sv[ab][v] == -INFINITY ? 0.f : exp_neg(sv[ab][v] - m_new);   // masked keys: 0
-                    lsum += p;
-                    // this lane's column carries term r / 5 of query r % 5: p, p - t0 or p - t0 - t1
-                    const float r1 = p - rne_bf16(p);
-                    const float r2 = r1 - rne_bf16(r1);
-                    hv[4 * ab + v] = f32_to_bf16_bits(sel0 * p + sel1 * r1 + sel2 * r2);
+                    for (int v = 0; v < 4; ++v) {
+                        const float p = sv[ab][v] == -INFINITY ? 0.f : exp_neg(sv[ab][v] - m_new);   // masked keys: 0
+                        lsum += p;
+                        // this lane's column carries term r / 5 of query r % 5: p, p - t0 or p - t0 - t1
+                        const float r1 = p - rne_bf16(p);
+                        const float r2 = r1 - rne_bf16(r1);
+                        hv[4 * ab + v] = f32_to_bf16_bits(sel0 * p + sel1 * r1 + sel2 * r2);
+                    }
+                const uint4 pb = uint4{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16), hv[4] | (hv[5] << 16), hv[6] | (hv[7] << 16)};
+                lsum += __shfl_xor(lsum, 16);
+                lsum += __shfl_xor(lsum, 32);
+                l_run[qg] = l_run[qg] * rescale + lsum;
+                m_run[qg] = m_new;
+#pragma unroll
+                for (int i = 0; i < NDT; ++i) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc_o[qg][i][v] *= rescale;
+                    acc_o[qg][i] = mfma16(vreg[s][i], pb, acc_o[qg][i]);
                 }
-            const uint4 pb = uint4{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16), hv[4] | (hv[5] << 16), hv[6] | (hv[7] << 16)};
-            lsum += __shfl_xor(lsum, 16);
-            lsum += __shfl_xor(lsum, 32);
-            l_run = l_run * rescale + lsum;
-            m_run = m_new;
-#pragma unroll
-            for (int i = 0; i < NDT; ++i) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v) acc_o[i][v] *= rescale;
-                acc_o[i] = mfma16(vreg[s][i], pb, acc_o[i]);
             }
         }
     }
     // partial of this wave: O[dim 16 i + 4 g + v][column r]; the three term columns summed
 #pragma unroll
-    for (int i = 0; i < NDT; ++i)
+    for (int qg = 0; qg < QG; ++qg) {
+        const int m = qg * kGroupRows + r;            // query of this lane's column (rows beyond 7 do not exist)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const float x = sum_terms(acc_o[i][v]);
-            if (r < kGroupRows) part_o[w][r][16 * i + 4 * g + v] = x;
-        }
-    if (lane < kGroupRows) { part_m[w][lane] = m_run; part_l[w][lane] = l_run; }
+        for (int i = 0; i < NDT; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float x = sum_terms(acc_o[qg][i][v]);
+                if (r < kGroupRows && m < 8) part_o[w][m][16 * i + 4 * g + v] = x;
+            }
+        if (lane < kGroupRows && m < 8) { part_m[w][m] = m_run[qg]; part_l[w][m] = l_run[qg]; }
+    }
 
     // ---- the M new keys (causal among the new rows), float32 from LDS -----------------------
     if (w == 0) {                                   // wave 0 owns the fewest key units

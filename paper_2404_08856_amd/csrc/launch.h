@@ -95,7 +95,7 @@ struct AttnArgs {
                              // positions, so that the dh x 32 tile one unit of 32 keys needs is 64 * dh contiguous bytes
     void *xout;              // packed activations, K = H * dh (attention output)
     int n_seqs, M, H, dh, max_positions, v_stride;
-    int m0, Mq;              // this launch handles rows m0 .. m0 + Mq - 1 of every sequence (Mq <= 5); rows
+    int m0, Mq;              // this launch handles rows m0 .. m0 + Mq - 1 of every sequence (Mq <= 8); rows
                              // 0 .. m0 - 1 were appended to the cache by an earlier launch
     const int32_t *d_lens;   // KV lengths in device memory [n_seqs], or NULL: then `lens` below holds them
     int32_t *d_error;        // set to 1 if a device length does not leave room for M rows (the launch then

@@ -494,8 +494,8 @@ int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const flo
             g.W = m->packed + L.wqkv[l]; g.X = xn; g.N = 3 * HD; g.K = d; g.rows = rows; g.Y = qkv; g.ldy = 3 * HD;
             g.ssq_in = ssq_b; g.ssq_in_parts = (l == 0) ? 1 : d_tiles; g.eps = c.rms_eps;
             PROF_GEMM(PK_QKV, launch_gemm(g, EPI_STORE, m->t_qkv, st));
-            for (int m0 = 0; m0 < M; m0 += kGroupRows) {         // at most 5 queries per sequence and launch
-                at.m0 = m0; at.Mq = std::min(kGroupRows, M - m0);
+            for (int m0 = 0; m0 < M; m0 += 8) {         // at most 8 queries per sequence and launch
+                at.m0 = m0; at.Mq = std::min(8, M - m0);
                 PROF_TRY(PK_ATTENTION, launch_attention(at, st));
             }
         }

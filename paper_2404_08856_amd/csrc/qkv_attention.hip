@@ -117,7 +117,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void qkv_attention_kernel(QkvAttnA
         }
         __syncthreads();
     };
-    attention_core<DH, S, kAttnWaves, kUnitsPerIter, true>(a.at, hh, ds, 0, wait_head);
+    attention_core<DH, S, kAttnWaves, kUnitsPerIter, true, 1>(a.at, hh, ds, 0, wait_head);
 }
 
 bool qkv_attention_supported(int K, int H, int dh, int rows, int n_seqs, int M) {
