@@ -362,6 +362,25 @@ def batched_verify(args, spd, synth, torch):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / reps
         res[f"batch_{B}"] = {"ms_per_step": ms, "verified_tokens_per_s": B * M / (ms * 1e-3)}
+    # one sequence at other draft lengths (gamma + 1 = 4, 6, 8 tokens per call)
+    for Mg in (4, 6, 8):
+        vt = torch.from_numpy(synth.text_tokens(Mg, ts.vocab, args.seed + 31).reshape(1, Mg)).cuda()
+        out = torch.empty((1, Mg, ts.vocab), dtype=torch.float32, device="cuda")
+
+        def step_g():
+            model.spd_kv_set_len([n_prefix])
+            model.spd_verify_forward(vt, out)
+
+        for _ in range(3):
+            step_g()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(20):
+            step_g()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 20
+        res[f"gamma_{Mg - 1}"] = {"ms_per_step": ms, "verified_tokens_per_s": Mg / (ms * 1e-3)}
     model.close()
     return res
 
