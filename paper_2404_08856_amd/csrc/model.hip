@@ -164,6 +164,7 @@ struct spd_model {
     std::vector<int32_t> lens;         // KV lengths (host).  With dev_lens: only an upper bound
     bool dev_lens = false;             // the kernels read the lengths from device memory (ws + L.d_lens)
     bool fuse_qa = false;              // QKV projection + attention as one kernel where the shape allows it
+    bool fuse_qa2 = false;             // ... also for 6..8 rows of one sequence
     unsigned qa_count = 0;             // value of that kernel's per-head arrival counters after the last launch
     std::vector<float> rope_host;
     GemmTuning t_qkv, t_o, t_gu, t_down, t_lm;
@@ -332,6 +333,7 @@ int32_t spd_model_create(const spd_model_config *cfg, const spd_weights *w, void
     // gaps of the per-stage kernels they remove, so the per-stage path is the default.
     // fused QKV + attention (SPD_NO_FUSE=1 keeps the two kernels)
     m->fuse_qa = !getenv("SPD_NO_FUSE") && qkv_attention_supported(cfg->d_model, cfg->n_heads, cfg->head_dim, 1, 1, 1);
+    m->fuse_qa2 = m->fuse_qa && qkv_attention_supported(cfg->d_model, cfg->n_heads, cfg->head_dim, 8, 1, 8);
     m->mega_grid = 0;
     if (getenv("SPD_MEGA") && cfg->n_layers > 0) m->mega_grid = megakernel_max_grid(cfg->head_dim);
     if (const char *e = getenv("SPD_MEGA_GRID")) { int g = atoi(e); if (g > 0 && g < m->mega_grid) m->mega_grid = g; }
@@ -471,7 +473,7 @@ int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const flo
     at.n_seqs = n_seqs; at.M = M; at.H = c.n_heads; at.dh = c.head_dim; at.max_positions = c.max_positions;
     at.v_stride = L.v_stride;
 
-    const bool fused = m->fuse_qa && rows <= kGroupRows && n_seqs == 1;   // the shape was checked at creation
+    const bool fused = m->fuse_qa && n_seqs == 1 && (rows <= kGroupRows || (rows <= 8 && m->fuse_qa2));   // shapes checked at creation
     for (int l = 0; l < c.n_layers; ++l) {
         // RMSNorm is folded into the projections: the producer of h (input rows / O / down
         // epilogue) leaves packed (h * gain) and per-tile sums of squares; the consumer

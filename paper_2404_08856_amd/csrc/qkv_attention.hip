@@ -24,9 +24,13 @@ __device__ __forceinline__ uint4 qa_load_stream(const uint4 *p) {
     return uint4{v.x, v.y, v.z, v.w};
 }
 
-template <int DH>
-__global__ __launch_bounds__(kAttnWaves * 64) void qkv_attention_kernel(QkvAttnArgs a) {
+// NG = 1: up to 5 rows; 12 waves, 8 of which stream the projection.  NG = 2: 6..10 rows of one sequence
+// (its attention then handles up to 8 of them as two query groups); 8 waves, all in both parts -- the
+// second activation slice needs the registers that a wider workgroup would not leave.
+template <int DH, int NG>
+__global__ __launch_bounds__((NG == 1 ? kAttnWaves : kQaGemmWaves) * 64) void qkv_attention_kernel(QkvAttnArgs a) {
     constexpr int S = DH / 16, GW = kQaGemmWaves, NB = kQaNB, U = kQaRing, KS = GW * NB;
+    constexpr int TW = NG == 1 ? kAttnWaves : kQaGemmWaves;      // waves of the workgroup
     const int H = a.at.H, HD = H * DH;
     const int hh = blockIdx.x % H, ds = blockIdx.x / H;
     const int lane = threadIdx.x & 63;
@@ -36,25 +40,30 @@ __global__ __launch_bounds__(kAttnWaves * 64) void qkv_attention_kernel(QkvAttnA
     float *Y = const_cast<float *>(a.at.qkv);
     const int ldy = 3 * HD;
 
-    __shared__ float red[2][GW][16][8];
+    __shared__ float red[2][GW][NG][16][8];
 
     // ---- projection: tiles q, k, v of (head, slice) ---------------------------------------
     const int tile0 = hh * S + ds, tstride = HD / 16;
     const int s0 = w * NB;
-    uint4 av[U], bv[NB];
+    uint4 av[U], bv[NG][NB];
     if (w < GW) {
 #pragma unroll
         for (int u = 0; u < U; ++u) av[u] = qa_load_stream(W + ((size_t)tile0 * KS + s0 + u) * 64 + lane);
 #pragma unroll
-        for (int i = 0; i < NB; ++i) bv[i] = X[(size_t)(s0 + i) * 64 + lane];
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int i = 0; i < NB; ++i) bv[g][i] = X[((size_t)g * KS + s0 + i) * 64 + lane];
     }
-    const int en = lane & 15, em = (w & 1) * 4 + (lane >> 4);          // epilogue element of this thread
-    const bool row_ok = em < a.rows;
+    // epilogue element of this thread: waves 2 NG j' .. 2 NG j' + 2 NG - 1 finish a tile, a pair per row group
+    const int en = lane & 15, em = (w & 1) * 4 + (lane >> 4);
+    const int eg = (w >> 1) % NG;                                      // row group of this wave's pair
+    const int erow = eg * kGroupRows + em;
+    const bool row_ok = em < kGroupRows && erow < a.rows;
     float inv_row = 1.0f;
     if (a.ssq_in && w < GW) {
         float sum = 0.f;
         if (row_ok) {
-            const float *part = a.ssq_in + (size_t)em * (KS * 2);
+            const float *part = a.ssq_in + (size_t)erow * (KS * 2);
             if ((a.ssq_in_parts & 3) == 0) {
 #pragma unroll 4
                 for (int p = en; p < (a.ssq_in_parts >> 2); p += 16) {
@@ -74,27 +83,32 @@ __global__ __launch_bounds__(kAttnWaves * 64) void qkv_attention_kernel(QkvAttnA
     for (int j = 0; j < 3; ++j) {
         const int t = tile0 + j * tstride;
         if (w < GW) {
-            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+            f32x4_t acc[NG];
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             const uint4 *wnext = (j < 2) ? W + ((size_t)(t + tstride) * KS + s0) * 64 : X;   // last tile: harmless re-read
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
-                acc = qa_mfma(av[i % U], bv[i], acc);
+#pragma unroll
+                for (int g = 0; g < NG; ++g) acc[g] = qa_mfma(av[i % U], bv[g][i], acc[g]);
                 if (i + U < NB) av[i % U] = qa_load_stream(W + ((size_t)t * KS + s0 + i + U) * 64 + lane);
                 else av[i % U] = qa_load_stream(wnext + (size_t)(j < 2 ? (i + U - NB) : 0) * 64 + lane);
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float x = sum_terms(acc[v]);
-                if ((lane & 15) < kGroupRows) red[j & 1][w][4 * (lane >> 4) + v][lane & 15] = x;
-            }
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float x = sum_terms(acc[g][v]);
+                    if ((lane & 15) < kGroupRows) red[j & 1][w][g][4 * (lane >> 4) + v][lane & 15] = x;
+                }
         }
         __syncthreads();
-        if ((w >> 1) == j && row_ok) {                     // waves 2 j and 2 j + 1 finish tile j
+        if (w < GW && (w / (2 * NG)) == (j % (GW / (2 * NG))) && row_ok) {   // 2 NG waves finish tile j
             float sum = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < GW; ++ww) sum += red[j & 1][ww][en][em];
-            __hip_atomic_store(Y + (size_t)em * ldy + (size_t)t * 16 + en, sum * inv_row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int ww = 0; ww < GW; ++ww) sum += red[j & 1][ww][eg][en][em];
+            __hip_atomic_store(Y + (size_t)erow * ldy + (size_t)t * 16 + en, sum * inv_row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     // the slices are written through to memory; once acknowledged, count this workgroup in
@@ -117,24 +131,27 @@ __global__ __launch_bounds__(kAttnWaves * 64) void qkv_attention_kernel(QkvAttnA
         }
         __syncthreads();
     };
-    attention_core<DH, S, kAttnWaves, kUnitsPerIter, true, 1>(a.at, hh, ds, 0, wait_head);
+    attention_core<DH, S, TW, kUnitsPerIter, true, NG>(a.at, hh, ds, 0, wait_head);
 }
 
 bool qkv_attention_supported(int K, int H, int dh, int rows, int n_seqs, int M) {
-    if (K != 32 * kQaGemmWaves * kQaNB || dh != 128 || rows > kGroupRows || n_seqs != 1 || M != rows) return false;
+    if (K != 32 * kQaGemmWaves * kQaNB || dh != 128 || rows > 8 || n_seqs != 1 || M != rows) return false;
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return false;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, qkv_attention_kernel<128>, kAttnWaves * 64, 0) != hipSuccess) return false;
-    return per_cu >= 1 && H * (dh / 16) <= cus * per_cu;   // all workgroups resident at once
+    hipError_t e = rows <= kGroupRows
+        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, qkv_attention_kernel<128, 1>, kAttnWaves * 64, 0)
+        : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, qkv_attention_kernel<128, 2>, kQaGemmWaves * 64, 0);
+    return e == hipSuccess && per_cu >= 1 && H * (dh / 16) <= cus * per_cu;   // all workgroups resident at once
 }
 
 hipError_t launch_qkv_attention(const QkvAttnArgs &a, hipStream_t stream) {
     const AttnArgs &t = a.at;
-    if (a.K != 32 * kQaGemmWaves * kQaNB || t.dh != 128 || a.rows < 1 || a.rows > kGroupRows || t.n_seqs != 1 || t.M != a.rows ||
+    if (a.K != 32 * kQaGemmWaves * kQaNB || t.dh != 128 || a.rows < 1 || a.rows > 8 || t.n_seqs != 1 || t.M != a.rows ||
         t.m0 != 0 || t.Mq != t.M || (t.v_stride % 32) != 0 || t.v_stride < t.max_positions || t.M > t.max_positions)
         return hipErrorInvalidValue;
-    launch_kernel(qkv_attention_kernel<128>, dim3(t.H * (t.dh / 16)), dim3(kAttnWaves * 64), stream, a);
+    if (a.rows <= kGroupRows) launch_kernel(qkv_attention_kernel<128, 1>, dim3(t.H * (t.dh / 16)), dim3(kAttnWaves * 64), stream, a);
+    else launch_kernel(qkv_attention_kernel<128, 2>, dim3(t.H * (t.dh / 16)), dim3(kQaGemmWaves * 64), stream, a);
     return hipGetLastError();
 }
 

@@ -299,7 +299,7 @@ def test_batched_verify_many_row_groups(n_seqs, M):
 
 @pytest.mark.parametrize("dev_lens", [False, True])
 @pytest.mark.parametrize("fuse", [True, False])
-@pytest.mark.parametrize("M", [1, 5])
+@pytest.mark.parametrize("M", [1, 5, 6, 8])
 def test_qkv_attention_fused_and_separate_kernels(fuse, M, dev_lens, monkeypatch):
     """d_model 4096 with 2 heads of 128: the shape class that takes the fused QKV + attention kernel
     (one workgroup per head and 16 output dimensions, per-head arrival counter), against the
