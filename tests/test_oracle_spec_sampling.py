@@ -421,3 +421,96 @@ def test_mbsu_reading_reproduces_the_papers_scale():
         assert c * (gamma + 1) / (c * gamma + 1) < 1.0          # upper bound of the printed form
     assert metrics.mbsu(4.0, 0.0, 3) == 4.0                      # free draft: speed-up = tau
     assert metrics.mbsu(1.0, 1.0, 1) == 0.5                      # draft as costly as target, nothing accepted
+
+
+# --------------------------------------------------------------------------------------
+# conditioning history of the block loop (Section 2.1: d_j ~ D(. | X_1:n, d_1..d_{j-1}),
+# T_j = T(. | V_1:m, X_1:n, d_1..d_{j-1}); Section 3: the draft sees the text only)
+# --------------------------------------------------------------------------------------
+
+def history_pin_max_error(result, target, draft, image_rows, text_tokens, first_token, gamma):
+    """Largest deviation of any stored draft / target row of spd_generate from a FRESH recompute
+    (empty cache) over the true history: the prompt, every token emitted so far and this block's
+    drafted tokens before the row.  Nothing here uses a KV cache, a truncation or a rollback."""
+    (tc, tw), (dc, dw) = target, draft
+    worst = 0.0
+    emitted = [int(first_token)]                       # tokens committed so far; the last one is t
+    for blk in result["blocks"]:
+        d = [int(x) for x in blk["draft_tokens"]]
+        text_hist = [int(x) for x in text_tokens] + emitted
+        for j in range(gamma):
+            # draft: text prompt + committed tokens + d_1..d_{j-1}, text only, positions from 0
+            x = dec.embed_tokens(dw, np.array(text_hist + d[:j], dtype=np.int64))
+            D_ref = ss.softmax_probs(dec.full_recompute(dc, dw, x)[-1], 1.0)
+            worst = max(worst, float(np.max(np.abs(blk["D"][j].astype(np.float64) - D_ref.astype(np.float64)) /
+                                            (D_ref.astype(np.float64) + 1e-9))))
+        for j in range(gamma + 1):
+            # target: [image rows ; E[text prompt + committed + d_1..d_{j-1}]]
+            x = dec.embed_tokens(tw, np.array(text_hist + d[:j], dtype=np.int64))
+            if image_rows is not None:
+                x = np.concatenate([np.asarray(image_rows, dtype=np.float64), x])
+            T_ref = ss.softmax_probs(dec.full_recompute(tc, tw, x)[-1], 1.0)
+            worst = max(worst, float(np.max(np.abs(blk["T"][j].astype(np.float64) - T_ref.astype(np.float64)) /
+                                            (T_ref.astype(np.float64) + 1e-9))))
+        emitted = emitted + d[:blk["k"]] + [int(blk["y"])]
+    return worst
+
+
+def run_history_case(gamma, seed):
+    target, draft = aligned_pair(seed)
+    img = synth.image_rows(5, 256, seed)
+    toks = synth.text_tokens(7, 1024, seed)
+    n_new = 14
+    ud = synth.uniforms((n_new, gamma), seed + 1)
+    ua = synth.uniforms((n_new, gamma + 1), seed + 2)
+    res = ss.spd_generate(target, draft, img, toks, gamma, n_new, 1.0, np.float32(0.41), ud, ua)
+    first = res["tokens"][0]
+    return res, history_pin_max_error(res, target, draft, img, toks, first, gamma)
+
+
+@pytest.mark.parametrize("gamma,seed", [(3, 0), (4, 5)])
+def test_block_loop_rows_condition_on_the_true_history(gamma, seed):
+    """Every D_j and T_j the block loop produces equals a recompute from scratch over the
+    prompt + emitted tokens + d_1..d_{j-1} (the draft without the image rows): pins the cache
+    bookkeeping of both models (rollback after a rejection, two pending tokens after a full
+    acceptance, draft positions = text positions)."""
+    res, worst = run_history_case(gamma, seed)
+    ks = [b["k"] for b in res["blocks"]]
+    assert max(ks) == gamma and min(ks) < gamma, ks          # full acceptance and rejection both occur
+    assert len(res["blocks"]) >= 3
+    assert worst < 1e-6, worst                               # float32 rows of float64 softmaxes: ~1e-7 apart
+
+
+@pytest.mark.parametrize("which", ["draft_one_short", "draft_one_long", "target_one_short"])
+def test_history_pin_detects_a_planted_cache_off_by_one(which, monkeypatch):
+    """The pin above must fail for a plausible bookkeeping mistake: a rollback that leaves a
+    cache one position short or long (planted in the oracle's cache class, on the CPU)."""
+    orig = dec.KVCache.truncate
+    state = {"calls": 0}
+
+    def bad(self, length):
+        is_draft = state.get("draft_id") == id(self)
+        shift = 0
+        if which == "draft_one_short" and is_draft:
+            shift = -1
+        elif which == "draft_one_long" and is_draft and length < self.length:
+            shift = 1
+        elif which == "target_one_short" and not is_draft:
+            shift = -1
+        state["calls"] += 1
+        orig(self, length + shift)
+
+    orig_init = dec.KVCache.__init__
+    made = []
+
+    def init(self, cfg, max_positions):
+        orig_init(self, cfg, max_positions)
+        made.append(self)
+        if len(made) == 2:                              # spd_generate builds the target's cache, then the draft's
+            state["draft_id"] = id(self)
+
+    monkeypatch.setattr(dec.KVCache, "__init__", init)
+    monkeypatch.setattr(dec.KVCache, "truncate", bad)
+    res, worst = run_history_case(3, 0)
+    assert state["calls"] > 0
+    assert worst > 1e-3, worst
