@@ -26,7 +26,7 @@
  *   - All device work is enqueued on the caller's hipStream_t, passed as void*
  *     (NULL = the default stream).  No call synchronises the device, except the few
  *     whose comment says so (spd_kv_lens_to_device / _from_device, spd_device_status,
- *     spd_trace_read, spd_trace_stages).
+ *     spd_trace_read).
  *   - The library allocates no device memory: weights (packed), KV cache and
  *     workspace live in caller-owned buffers whose sizes spd_model_bytes()
  *     reports.  The model borrows them until spd_model_destroy().
@@ -110,6 +110,25 @@ int32_t spd_model_create(const spd_model_config *h_cfg, const spd_weights *h_wei
                          spd_model **h_out);
 
 int32_t spd_model_destroy(spd_model *model);
+
+/* Kernel-selection knobs of a model, for tests and sweeps (not part of the method; production
+ * code never needs this call: spd_model_create picks the measured defaults).  Zero-initialise the
+ * struct for "all defaults".  Takes effect from the next forward; host-side only.
+ * Projections are indexed qkv, o, gate_up, down, lm_head. */
+#define SPD_N_PROJECTIONS 5
+typedef struct {
+    int32_t  separate_qkv_attention; /* 1: QKV projection and attention always as two kernels;
+                                        0 = default: one kernel where the shape allows */
+    int32_t  attention_slices;       /* workgroups per head of the stand-alone attention kernel at head_dim 128:
+                                        1, 2, 4 or 8; 0 = chosen by batch size */
+    int32_t  gemm_waves[SPD_N_PROJECTIONS];          /* waves per workgroup: 4, 8 or 16; 0 = default */
+    int32_t  gemm_grid_cap[SPD_N_PROJECTIONS];       /* upper bound of the grid; 0 = default         */
+    int32_t  gemm_general_kernel[SPD_N_PROJECTIONS]; /* 1: never the register-resident variant       */
+    uint32_t wait_spin_limit;        /* polls before a wait between workgroups gives up and raises the flag that
+                                        spd_device_status reports (0 = default, 2^22); a tiny value lets a test
+                                        drive that error path from the host while every kernel still exits */
+} spd_tuning;
+int32_t spd_model_set_tuning(spd_model *model, const spd_tuning *h_tuning);
 
 /* Sets the number of valid KV positions of sequences 0..n_seqs-1 (rollback
  * after a rejection, reset to 0, ...).  Host-side bookkeeping only: positions
@@ -199,8 +218,7 @@ int32_t spd_speculative_accept(const float *target, const float *draft, const in
  * works on a clamped length (every access stays in bounds, the results are meaningless) and
  * raises a flag that spd_kv_lens_from_device reports as SPD_ERR_CAPACITY.  Both calls wait
  * for `stream` (they are the only ones besides spd_trace_* that block).  spd_kv_set_len is
- * refused while the lengths live on the device.  The whole-forward persistent kernel is
- * not used in this mode. */
+ * refused while the lengths live on the device. */
 int32_t spd_kv_lens_to_device(spd_model *model, void *stream);
 int32_t spd_kv_lens_from_device(spd_model *model, void *stream);
 
@@ -237,8 +255,8 @@ int32_t spd_block_finish(spd_model *target, spd_model *draft, const float *targe
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /* Waits for `stream` and reports conditions that kernels can only flag on the device:
- * SPD_ERR_HIP if a bounded wait between workgroups (fused QKV + attention kernel, whole-forward
- * kernel) ever ran into its spin limit -- never in a healthy run; results since then are
+ * SPD_ERR_HIP if a bounded wait between workgroups (fused QKV + attention kernel) ever ran
+ * into its spin limit -- never in a healthy run; results since then are
  * invalid --, SPD_ERR_CAPACITY if a forward in device-length mode found no room for its rows,
  * else SPD_OK. */
 int32_t spd_device_status(spd_model *model, void *stream);
@@ -253,20 +271,11 @@ int32_t spd_device_status(spd_model *model, void *stream);
  * the recorded events (the one call here that blocks the host), adds the elapsed
  * milliseconds and launch counts per kind into h_ms_sum[n_kinds] / h_count[n_kinds] and
  * forgets them.  Kinds: 0 QKV projection, 1 O projection, 2 gate|up projection + SwiGLU,
- * 3 down projection, 4 LM head, 5 RoPE + KV append + attention, 6 the whole forward as one
- * persistent kernel (calls of up to 5 rows; kinds 0-5 and 7 then stay empty), 7 input rows
- * (embedding gather).  The events perturb the stream slightly: time whole
- * steps with tracing off. */
-#define SPD_TRACE_KINDS 8
+ * 3 down projection, 4 LM head, 5 RoPE + KV append + attention, 6 input rows (embedding
+ * gather).  The events perturb the stream slightly: time whole steps with tracing off. */
+#define SPD_TRACE_KINDS 7
 int32_t spd_trace_enable(spd_model *model, int32_t enable);
 int32_t spd_trace_read(spd_model *model, int32_t n_kinds, double *h_ms_sum, int32_t *h_count);
-/* Stage timeline of the LAST whole-forward kernel launched while tracing was enabled.  Stage i
- * (input rows; per layer QKV, attention, O, gate|up, down; LM head) ends at device-wide barrier
- * i; for every barrier, in microseconds since the kernel's first workgroup started: when the
- * first and the last workgroup arrived at it and when the first and the last workgroup left
- * it.  Blocks the host (synchronous copy).  Each array: [max_stages]. */
-int32_t spd_trace_stages(spd_model *model, int32_t max_stages, double *h_first_arrive, double *h_last_arrive,
-                         double *h_first_leave, double *h_last_leave, int32_t *h_n_stages);
 
 #ifdef __cplusplus
 }

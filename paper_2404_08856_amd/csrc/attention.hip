@@ -1,6 +1,4 @@
 // Stand-alone attention kernel: RoPE + KV-cache append + causal attention (see attention_core.h).
-#include <cstdlib>
-
 #include "attention_core.h"
 
 namespace spd {
@@ -19,9 +17,8 @@ hipError_t launch_attention(const AttnArgs &a, hipStream_t stream) {
     // workgroup is fastest at the 7B shape (15.4 us per layer against 16.2 with 32 and 18.8 with 64).
     // More (sequence, head) pairs: every slice re-reads K, so as soon as the pairs alone fill the
     // chip the slices only cost (8 sequences, context 2048: 73 us per layer unsliced, 76 with 2,
-    // 108 with 4, 160 with 8 slices).  SPD_ATTN_SLICES overrides for head_dim 128.
-    const char *forced = getenv("SPD_ATTN_SLICES");
-    int slices = forced ? atoi(forced) : 0;
+    // 108 with 4, 160 with 8 slices).  a.slices (a tuning knob for tests and sweeps) overrides for head_dim 128.
+    int slices = a.slices;
     const int pairs = a.n_seqs * a.H;
     if (slices != 1 && slices != 2 && slices != 4 && slices != 8) slices = pairs >= 256 ? 1 : (pairs >= 128 ? 2 : (pairs >= 64 ? 4 : 8));
     if (slices == 1 && a.Mq > kGroupRows) slices = 2;   // two query groups and a whole head do not fit the registers

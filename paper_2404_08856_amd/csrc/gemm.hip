@@ -6,6 +6,7 @@
 // (common.h), each wave reads 1 KiB blocks with one coalesced load per block and
 // feeds them straight to v_mfma_f32_16x16x32_bf16; nothing goes through LDS except
 // the final cross-wave reduction of a 16 x 8 output tile.
+#include "gemm_core.h"
 #include "launch.h"
 
 namespace spd {
@@ -73,18 +74,6 @@ LaunchTiming *&launch_timing() {
 // ---------------------------------------------------------------------------------
 // GEMM
 // ---------------------------------------------------------------------------------
-__device__ __forceinline__ f32x4_t mfma_bf16(const uint4 &a, const uint4 &b, f32x4_t c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                   __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-}
-
-__device__ __forceinline__ uint4 load_stream(const uint4 *p) {
-    // weights are read exactly once per step: non-temporal loads (measured: +15% on a pure read stream)
-    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
-    u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
-    return uint4{v.x, v.y, v.z, v.w};
-}
-
 struct GemmKernelArgs {
     const uint4 *W;
     const uint4 *X;
@@ -443,23 +432,8 @@ __global__ __launch_bounds__(WAVES * 64, (NG > 1 ? 1 : (NB <= 8 ? 4 : 2))) void 
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
             const int row = g * kGroupRows + em;
-            // the row's partials are contiguous: 16 lanes read them as float4, all loads in flight at once
-            float sum = 0.f;
-            if (em < kGroupRows && row < a.rows) {
-                const float *part = a.ssq_in + (size_t)row * (KS * 2);
-                if ((a.ssq_in_parts & 3) == 0) {
-#pragma unroll 4
-                    for (int p = en; p < (a.ssq_in_parts >> 2); p += 16) {
-                        const float4 q = reinterpret_cast<const float4 *>(part)[p];
-                        sum += (q.x + q.y) + (q.z + q.w);
-                    }
-                } else {
-                    for (int p = en; p < a.ssq_in_parts; p += 16) sum += part[p];
-                }
-            }
-#pragma unroll
-            for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-            inv_row[g] = 1.0f / sqrtf(sum * a.inv_d + a.eps);
+            inv_row[g] = rms_inv_from_parts(a.ssq_in + (size_t)row * (KS * 2), a.ssq_in_parts, en,
+                                            em < kGroupRows && row < a.rows, a.inv_d, a.eps);
         }
     }
 
@@ -480,24 +454,10 @@ __global__ __launch_bounds__(WAVES * 64, (NG > 1 ? 1 : (NB <= 8 ? 4 : 2))) void 
         if (EPI == EPI_RESIDUAL && e_active) hold = a.Y[(size_t)erow * a.ldy + (size_t)t * 16 + en];
 
         f32x4_t acc[NG];
-#pragma unroll
-        for (int g = 0; g < NG; ++g) acc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        const uint4 *wnext = has_next ? a.W + ((size_t)tn * KS + s0) * 64 : a.X;   // past the end: harmless re-read
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-#pragma unroll
-            for (int g = 0; g < NG; ++g) acc[g] = mfma_bf16(av[i % U], bv[g][i], acc[g]);
-            if (i + U < NB) av[i % U] = load_stream(a.W + ((size_t)t * KS + s0 + i + U) * 64 + lane);
-            else av[i % U] = load_stream(wnext + (size_t)(has_next ? (i + U - NB) : 0) * 64 + lane);
-            __builtin_amdgcn_sched_barrier(0);            // keep "consume slot, refill slot" in program order
-        }
-#pragma unroll
-        for (int g = 0; g < NG; ++g)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float x = sum_terms(acc[g][v]);
-                if ((lane & 15) < kGroupRows) red[parity][w][g][4 * (lane >> 4) + v][lane & 15] = x;
-            }
+        const uint4 *wcur = a.W + ((size_t)t * KS + s0) * 64 + lane;
+        const uint4 *wnext = (has_next ? a.W + ((size_t)tn * KS + s0) * 64 : a.X) + lane;   // past the end: harmless re-read
+        regb_tile<NB, U, NG>(acc, av, bv, wcur, wnext, has_next);
+        store_partial<NG>(acc, red[parity][w], lane);
         __syncthreads();
         if (!my_turn) continue;
 

@@ -95,6 +95,7 @@ struct AttnArgs {
                              // positions, so that the dh x 32 tile one unit of 32 keys needs is 64 * dh contiguous bytes
     void *xout;              // packed activations, K = H * dh (attention output)
     int n_seqs, M, H, dh, max_positions, v_stride;
+    int slices;              // stand-alone kernel: workgroups per head (1, 2, 4, 8 for head_dim 128), 0 = chosen by batch size
     int m0, Mq;              // this launch handles rows m0 .. m0 + Mq - 1 of every sequence (Mq <= 8); rows
                              // 0 .. m0 - 1 were appended to the cache by an earlier launch
     const int32_t *d_lens;   // KV lengths in device memory [n_seqs], or NULL: then `lens` below holds them
@@ -118,42 +119,12 @@ struct QkvAttnArgs {
     int ssq_in_parts;
     float eps;
     AttnArgs at;              // at.qkv: float32 [rows][3 * H * dh] scratch filled by the projection part
-    unsigned *head_count;     // [H] arrival counters; every launch adds dh / 16 to each
-    unsigned count_before;    // their common value before this launch
+    unsigned *head_count;     // [H] arrival counters (only grow); every launch adds dh / 16 to each
+    unsigned spin_limit;      // polls of a counter before the wait gives up and raises abort_flag
     int *abort_flag;          // raised (and never cleared) if a wait hit its spin limit
 };
 bool qkv_attention_supported(int K, int H, int dh, int rows, int n_seqs, int M);
 hipError_t launch_qkv_attention(const QkvAttnArgs &a, hipStream_t stream);
-
-// ---- whole forward in one persistent kernel (rows <= 5) -------------------------------------
-struct MegaArgs {
-    // model
-    const char *packed;                       // packed weights (spd_model_create layout)
-    size_t off_embed, off_lm_head, off_final_norm;
-    size_t off_attn_norm0, off_wqkv0, off_wo0, off_mlp_norm0, off_wgu0, off_wdown0, layer_stride;
-    char *kv;                                 // KV cache: per layer K [seqs][H][pos][dh] then V^T [seqs][H][dh][v_stride]
-    size_t kv_layer_stride, kv_v_offset;
-    int n_layers, d, H, dh, F, V, max_positions, v_stride;
-    float eps;
-    const float *rope;
-    // workspace: float32 row-major arrays of 8 rows, exchanged between workgroups
-    float *h, *hg, *qkv, *att, *xf, *ssq_a, *ssq_b;    // ssq_*: [d / 16][8]
-    unsigned *bar;                            // arrival counter of the device-wide barrier (only grows)
-    int *abort_flag;                          // set if a barrier wait hit its spin limit
-    unsigned long long *stage_clock;          // NULL, or [grid][2 * (barriers + 1)] wall-clock stamps
-    // this call
-    const int32_t *tokens;                    // [rows] or NULL
-    const float *embeds;                      // [rows][d] or NULL
-    float *logits;                            // [rows][V] or NULL (skip the LM head)
-    int n_seqs, M, rows, seq0;
-    unsigned bar_base;                        // counter value before this launch
-    SeqLens lens;
-};
-// grid = number of CUs (one resident workgroup each); cooperative launch
-hipError_t launch_megakernel(const MegaArgs &a, int grid, hipStream_t stream);
-int megakernel_max_grid(int dh);              // 0 if the kernel cannot be made resident
-constexpr int kMegaBarriersPerLayer = 5;
-constexpr int kMegaMaxGrid = 1024;        // upper bound of the whole-forward kernel's grid (one workgroup per CU)
 
 // ---- sampling ---------------------------------------------------------------------
 struct AcceptArgs {

@@ -50,7 +50,6 @@ struct Layout {                    // byte offsets inside the three buffers
     int v_stride;
     // workspace
     size_t h, qkv, xn, xo, xf, rope, logits, ssq_a, ssq_b, d_lens, d_error, qa_count, qa_abort, ws_total;
-    size_t m_hg, m_att, m_xf, m_ssq_a, m_ssq_b, m_sync, m_clock;     // arrays of the whole-forward kernel (one row group)
 };
 
 int32_t check_shape(const spd_model_config &c) {
@@ -107,13 +106,6 @@ void make_layout(const spd_model_config &c, Layout &L) {
     L.qa_abort = take(4);
     L.ssq_a = take((size_t)(d / 16) * kMaxRows * 4);
     L.ssq_b = take((size_t)(d / 16) * kMaxRows * 4);
-    L.m_hg = take((size_t)8 * d * 4);
-    L.m_att = take((size_t)8 * HD * 4);
-    L.m_xf = take((size_t)8 * KSf * 32 * 4);
-    L.m_ssq_a = take((size_t)(d / 16) * 8 * 4);
-    L.m_ssq_b = take((size_t)(d / 16) * 8 * 4);
-    L.m_sync = take(256);
-    L.m_clock = take((size_t)kMegaMaxGrid * (2 * (2 + kMegaBarriersPerLayer * c.n_layers)) * 8);
     L.ws_total = off;
 }
 
@@ -135,26 +127,6 @@ GemmTuning default_tuning(int N, int K) {
     return t;
 }
 
-// SPD_TUNE="qkv:8:512:8,o:16:256:8,gu:4:1024:8,down:16:0:8,lm:8:0:16"  (waves:grid_cap:ring), for sweeps
-void env_tuning(const char *name, GemmTuning &t) {
-    const char *env = getenv("SPD_TUNE");
-    if (!env) return;
-    std::string s(env), key = std::string(name) + ":";
-    size_t p = 0;
-    while (p < s.size()) {
-        size_t q = s.find(',', p);
-        if (q == std::string::npos) q = s.size();
-        std::string item = s.substr(p, q - p);
-        if (item.compare(0, key.size(), key) == 0) {
-            int w = 0, cap = 0, ring = 8, noregb = 0;
-            if (sscanf(item.c_str() + key.size(), "%d:%d:%d:%d", &w, &cap, &ring, &noregb) >= 1) {
-                t.waves = w; t.grid_cap = cap; t.ring = ring; t.no_regb = noregb;
-            }
-        }
-        p = q + 1;
-    }
-}
-
 }  // namespace
 
 struct spd_model {
@@ -165,11 +137,11 @@ struct spd_model {
     bool dev_lens = false;             // the kernels read the lengths from device memory (ws + L.d_lens)
     bool fuse_qa = false;              // QKV projection + attention as one kernel where the shape allows it
     bool fuse_qa2 = false;             // ... also for 6..8 rows of one sequence
-    unsigned qa_count = 0;             // value of that kernel's per-head arrival counters after the last launch
+    bool fuse_qa_ok = false, fuse_qa2_ok = false;   // what the shape and the device allow (checked at creation)
+    int attn_slices = 0;               // workgroups per head of the stand-alone attention kernel (0: chosen by batch size)
+    unsigned spin_limit = 1u << 22;    // polls before a wait between workgroups gives up
     std::vector<float> rope_host;
     GemmTuning t_qkv, t_o, t_gu, t_down, t_lm;
-    int mega_grid = 0;                 // workgroups of the whole-forward kernel (0: not available)
-    unsigned bar_count = 0;            // value of the device-wide barrier counter after the last launch
     // optional tracing: HIP events around every launch group of a forward
     struct Span { int kind; hipEvent_t a, b; };
     bool prof_on = false;
@@ -188,7 +160,7 @@ struct spd_model {
 };
 
 namespace {
-enum ProfKind { PK_QKV = 0, PK_O, PK_GATE_UP, PK_DOWN, PK_LM_HEAD, PK_ATTENTION, PK_FORWARD, PK_EMBED, PK_COUNT };
+enum ProfKind { PK_QKV = 0, PK_O, PK_GATE_UP, PK_DOWN, PK_LM_HEAD, PK_ATTENTION, PK_EMBED, PK_COUNT };
 
 // Runs one launch group; when tracing is on, brackets it with events on the same stream (the interval
 // then includes the dispatch of the group's first kernel).
@@ -323,21 +295,45 @@ int32_t spd_model_create(const spd_model_config *cfg, const spd_weights *w, void
     CREATE_TRY(hipMemcpyAsync(m->ws + L.rope, m->rope_host.data(), m->rope_host.size() * 4, hipMemcpyHostToDevice, st));
 #undef CREATE_TRY
 
-    m->t_qkv = default_tuning(3 * HD, d);   env_tuning("qkv", m->t_qkv);
-    m->t_o = default_tuning(d, HD);         env_tuning("o", m->t_o);
-    m->t_gu = default_tuning(2 * F, d);     env_tuning("gu", m->t_gu);
-    m->t_down = default_tuning(d, F);       env_tuning("down", m->t_down);
-    m->t_lm = default_tuning(V, d);         env_tuning("lm", m->t_lm);
-    // Whole-forward persistent kernel for calls of up to 5 rows.  Opt-in (SPD_MEGA=1): at the 7B
-    // shape its device-wide barriers and lock-step stages currently cost more than the launch
-    // gaps of the per-stage kernels they remove, so the per-stage path is the default.
-    // fused QKV + attention (SPD_NO_FUSE=1 keeps the two kernels)
-    m->fuse_qa = !getenv("SPD_NO_FUSE") && qkv_attention_supported(cfg->d_model, cfg->n_heads, cfg->head_dim, 1, 1, 1);
-    m->fuse_qa2 = m->fuse_qa && qkv_attention_supported(cfg->d_model, cfg->n_heads, cfg->head_dim, 8, 1, 8);
-    m->mega_grid = 0;
-    if (getenv("SPD_MEGA") && cfg->n_layers > 0) m->mega_grid = megakernel_max_grid(cfg->head_dim);
-    if (const char *e = getenv("SPD_MEGA_GRID")) { int g = atoi(e); if (g > 0 && g < m->mega_grid) m->mega_grid = g; }
+    m->t_qkv = default_tuning(3 * HD, d);
+    m->t_o = default_tuning(d, HD);
+    m->t_gu = default_tuning(2 * F, d);
+    m->t_down = default_tuning(d, F);
+    m->t_lm = default_tuning(V, d);
+    // QKV projection + attention as one kernel where the shape and the device allow it
+    m->fuse_qa_ok = qkv_attention_supported(cfg->d_model, cfg->n_heads, cfg->head_dim, 1, 1, 1);
+    m->fuse_qa2_ok = m->fuse_qa_ok && qkv_attention_supported(cfg->d_model, cfg->n_heads, cfg->head_dim, 8, 1, 8);
+    m->fuse_qa = m->fuse_qa_ok;
+    m->fuse_qa2 = m->fuse_qa2_ok;
     *out = m;
+    return SPD_OK;
+}
+
+int32_t spd_model_set_tuning(spd_model *m, const spd_tuning *t) {
+    if (!m || !t) return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_model_set_tuning");
+    if (t->separate_qkv_attention != 0 && t->separate_qkv_attention != 1) return fail(SPD_ERR_INVALID_ARG, "separate_qkv_attention must be 0 or 1");
+    if (t->attention_slices != 0 && t->attention_slices != 1 && t->attention_slices != 2 && t->attention_slices != 4 &&
+        t->attention_slices != 8)
+        return fail(SPD_ERR_INVALID_ARG, "attention_slices must be 0, 1, 2, 4 or 8");
+    GemmTuning *gt[SPD_N_PROJECTIONS] = {&m->t_qkv, &m->t_o, &m->t_gu, &m->t_down, &m->t_lm};
+    for (int i = 0; i < SPD_N_PROJECTIONS; ++i) {
+        const int w = t->gemm_waves[i];
+        if (w != 0 && w != 4 && w != 8 && w != 16) return fail(SPD_ERR_INVALID_ARG, "gemm_waves must be 0, 4, 8 or 16");
+        if (t->gemm_grid_cap[i] < 0 || t->gemm_grid_cap[i] > 65535) return fail(SPD_ERR_INVALID_ARG, "gemm_grid_cap out of range");
+    }
+    const spd_model_config &c = m->cfg;
+    const int d = c.d_model, HD = c.n_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
+    const int Ns[SPD_N_PROJECTIONS] = {3 * HD, d, 2 * F, d, V}, Ks[SPD_N_PROJECTIONS] = {d, HD, d, F, d};
+    for (int i = 0; i < SPD_N_PROJECTIONS; ++i) {
+        *gt[i] = default_tuning(Ns[i], Ks[i]);
+        if (t->gemm_waves[i]) gt[i]->waves = t->gemm_waves[i];
+        gt[i]->grid_cap = t->gemm_grid_cap[i];
+        gt[i]->no_regb = t->gemm_general_kernel[i] ? 1 : 0;
+    }
+    m->fuse_qa = t->separate_qkv_attention ? false : m->fuse_qa_ok;
+    m->fuse_qa2 = t->separate_qkv_attention ? false : m->fuse_qa2_ok;
+    m->attn_slices = t->attention_slices;
+    m->spin_limit = t->wait_spin_limit ? t->wait_spin_limit : (1u << 22);
     return SPD_OK;
 }
 
@@ -383,12 +379,11 @@ int32_t spd_kv_lens_from_device(spd_model *m, void *stream) {
 
 int32_t spd_device_status(spd_model *m, void *stream) {
     if (!m) return fail(SPD_ERR_INVALID_ARG, "NULL model");
-    int32_t flags[3] = {0, 0, 0};
+    int32_t flags[2] = {0, 0};
     HIP_TRY(hipMemcpyAsync(&flags[0], m->ws + m->L.d_error, 4, hipMemcpyDeviceToHost, (hipStream_t)stream));
     HIP_TRY(hipMemcpyAsync(&flags[1], m->ws + m->L.qa_abort, 4, hipMemcpyDeviceToHost, (hipStream_t)stream));
-    HIP_TRY(hipMemcpyAsync(&flags[2], m->ws + m->L.m_sync + 64, 4, hipMemcpyDeviceToHost, (hipStream_t)stream));
     HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
-    if (flags[1] || flags[2]) return fail(SPD_ERR_HIP, "a wait between workgroups hit its spin limit: results since then are invalid");
+    if (flags[1]) return fail(SPD_ERR_HIP, "a wait between workgroups hit its spin limit: results since then are invalid");
     if (flags[0]) return fail(SPD_ERR_CAPACITY, "a forward ran with a device KV length that left no room for its rows");
     return SPD_OK;
 }
@@ -430,31 +425,6 @@ int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const flo
         at.d_error = (int32_t *)(m->ws + L.d_error);
     }
     const int d = c.d_model, HD = c.n_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
-    if (rows <= kGroupRows && m->mega_grid > 0 && !m->dev_lens) {
-        MegaArgs ma{};
-        ma.packed = m->packed;
-        ma.off_embed = L.embed; ma.off_lm_head = L.lm_head; ma.off_final_norm = L.final_norm;
-        ma.off_attn_norm0 = L.attn_norm[0]; ma.off_wqkv0 = L.wqkv[0]; ma.off_wo0 = L.wo[0];
-        ma.off_mlp_norm0 = L.mlp_norm[0]; ma.off_wgu0 = L.wgu[0]; ma.off_wdown0 = L.wdown[0];
-        ma.layer_stride = c.n_layers > 1 ? L.attn_norm[1] - L.attn_norm[0] : 0;
-        ma.kv = m->kv; ma.kv_layer_stride = L.kv_layer_stride; ma.kv_v_offset = align_up(L.kv_k_bytes, 256);
-        ma.n_layers = c.n_layers; ma.d = d; ma.H = c.n_heads; ma.dh = c.head_dim; ma.F = F; ma.V = V;
-        ma.max_positions = c.max_positions; ma.v_stride = L.v_stride; ma.eps = c.rms_eps;
-        ma.rope = (const float *)(m->ws + L.rope);
-        ma.h = (float *)(m->ws + L.h); ma.hg = (float *)(m->ws + L.m_hg); ma.qkv = (float *)(m->ws + L.qkv);
-        ma.att = (float *)(m->ws + L.m_att); ma.xf = (float *)(m->ws + L.m_xf);
-        ma.ssq_a = (float *)(m->ws + L.m_ssq_a); ma.ssq_b = (float *)(m->ws + L.m_ssq_b);
-        ma.bar = (unsigned *)(m->ws + L.m_sync); ma.abort_flag = (int *)(m->ws + L.m_sync + 64);
-        ma.tokens = tokens; ma.embeds = embeds; ma.logits = logits_out;
-        ma.n_seqs = n_seqs; ma.M = M; ma.rows = rows; ma.seq0 = seq0;
-        ma.bar_base = m->bar_count;
-        ma.stage_clock = m->prof_on ? (unsigned long long *)(m->ws + L.m_clock) : nullptr;
-        ma.lens = at.lens;
-        PROF_TRY(PK_FORWARD, launch_megakernel(ma, m->mega_grid, st));
-        m->bar_count += (unsigned)m->mega_grid * (unsigned)(1 + kMegaBarriersPerLayer * c.n_layers);
-        for (int s = 0; s < n_seqs; ++s) m->lens[seq0 + s] += M;
-        return SPD_OK;
-    }
     float *h = (float *)(m->ws + L.h);
     float *qkv = (float *)(m->ws + L.qkv);
     void *xn = m->ws + L.xn, *xo = m->ws + L.xo, *xf = m->ws + L.xf;
@@ -472,6 +442,7 @@ int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const flo
     at.xout = xo;
     at.n_seqs = n_seqs; at.M = M; at.H = c.n_heads; at.dh = c.head_dim; at.max_positions = c.max_positions;
     at.v_stride = L.v_stride;
+    at.slices = m->attn_slices;
 
     const bool fused = m->fuse_qa && n_seqs == 1 && (rows <= kGroupRows || (rows <= 8 && m->fuse_qa2));   // shapes checked at creation
     for (int l = 0; l < c.n_layers; ++l) {
@@ -488,10 +459,9 @@ int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const flo
             qa.ssq_in = ssq_b; qa.ssq_in_parts = (l == 0) ? 1 : d_tiles; qa.eps = c.rms_eps;
             at.m0 = 0; at.Mq = M;
             qa.at = at;
-            qa.head_count = (unsigned *)(m->ws + L.qa_count); qa.count_before = m->qa_count;
+            qa.head_count = (unsigned *)(m->ws + L.qa_count); qa.spin_limit = m->spin_limit;
             qa.abort_flag = (int *)(m->ws + L.qa_abort);
             PROF_KERNEL(PK_QKV, launch_qkv_attention(qa, st));
-            m->qa_count += (unsigned)(c.head_dim / 16);
         } else {
             g.W = m->packed + L.wqkv[l]; g.X = xn; g.N = 3 * HD; g.K = d; g.rows = rows; g.Y = qkv; g.ldy = 3 * HD;
             g.ssq_in = ssq_b; g.ssq_in_parts = (l == 0) ? 1 : d_tiles; g.eps = c.rms_eps;
@@ -569,31 +539,6 @@ int32_t spd_trace_read(spd_model *m, int32_t n_kinds, double *ms_sum, int32_t *c
         m->pool.push_back(sp.b);
     }
     m->spans.clear();
-    return SPD_OK;
-}
-
-int32_t spd_trace_stages(spd_model *m, int32_t max_stages, double *first_arrive, double *last_arrive,
-                         double *first_leave, double *last_leave, int32_t *n_stages) {
-    if (!m || !first_arrive || !last_arrive || !first_leave || !last_leave || !n_stages || max_stages < 1)
-        return fail(SPD_ERR_INVALID_ARG, "bad argument to spd_trace_stages");
-    if (m->mega_grid < 1) return fail(SPD_ERR_INVALID_ARG, "the whole-forward kernel is not enabled for this model");
-    const int n_bar = 1 + kMegaBarriersPerLayer * m->cfg.n_layers;            // barriers of one forward
-    const size_t n_stamps = (size_t)2 * (n_bar + 1), G = (size_t)m->mega_grid;
-    std::vector<unsigned long long> clk(G * n_stamps);
-    HIP_TRY(hipMemcpy(clk.data(), m->ws + m->L.m_clock, clk.size() * 8, hipMemcpyDeviceToHost));   // blocks
-    // per workgroup: [1] = start, [2 i] = arrival at barrier i, [2 i + 1] = departure from it (i >= 1)
-    unsigned long long t0 = ~0ull;
-    for (size_t g = 0; g < G; ++g) t0 = std::min(t0, clk[g * n_stamps + 1]);
-    *n_stages = n_bar < max_stages ? n_bar : max_stages;
-    for (int i = 0; i < *n_stages; ++i) {
-        unsigned long long a0 = ~0ull, a1 = 0, d0 = ~0ull, d1 = 0;
-        for (size_t g = 0; g < G; ++g) {
-            const unsigned long long arr = clk[g * n_stamps + 2 * i], dep = clk[g * n_stamps + 2 * (i + 1) + 1];
-            a0 = std::min(a0, arr); a1 = std::max(a1, arr); d0 = std::min(d0, dep); d1 = std::max(d1, dep);
-        }
-        first_arrive[i] = (double)(a0 - t0) * 0.01; last_arrive[i] = (double)(a1 - t0) * 0.01;
-        first_leave[i] = (double)(d0 - t0) * 0.01; last_leave[i] = (double)(d1 - t0) * 0.01;
-    }
     return SPD_OK;
 }
 

@@ -9,20 +9,19 @@
 // first, then the counter is awaited (bounded spin), then the head's new rows are read with
 // device-scope loads.  Every workgroup is resident at once (the grid is at most one workgroup
 // per CU and the kernel's resources allow one per CU), so every awaited arrival does happen.
+//
+// The arrival counters only grow, and what a workgroup waits for is derived on the device from
+// its own arrival: launches on one model are stream-ordered and each adds exactly S = dh / 16 to
+// every head's counter, so a counter is a multiple of S when a launch starts, the value the
+// arriving workgroup's atomic add returns is S * epoch + (arrivals before it), and the head is
+// complete at S * (epoch + 1).  Nothing about the count comes from the host, so a launch that
+// is replayed from a captured graph, or follows a capture that ran nothing, waits correctly.
 #include "attention_core.h"
+#include "gemm_core.h"
 
 namespace spd {
 
 constexpr int kQaGemmWaves = 8, kQaNB = 16, kQaRing = 8;
-
-__device__ __forceinline__ f32x4_t qa_mfma(const uint4 &a, const uint4 &b, f32x4_t c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-}
-__device__ __forceinline__ uint4 qa_load_stream(const uint4 *p) {
-    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
-    u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
-    return uint4{v.x, v.y, v.z, v.w};
-}
 
 // NG = 1: up to 5 rows; 12 waves, 8 of which stream the projection.  NG = 2: 6..10 rows of one sequence
 // (its attention then handles up to 8 of them as two query groups); 8 waves, all in both parts -- the
@@ -48,7 +47,7 @@ __global__ __launch_bounds__((NG == 1 ? kAttnWaves : kQaGemmWaves) * 64) void qk
     uint4 av[U], bv[NG][NB];
     if (w < GW) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) av[u] = qa_load_stream(W + ((size_t)tile0 * KS + s0 + u) * 64 + lane);
+        for (int u = 0; u < U; ++u) av[u] = load_stream(W + ((size_t)tile0 * KS + s0 + u) * 64 + lane);
 #pragma unroll
         for (int g = 0; g < NG; ++g)
 #pragma unroll
@@ -60,48 +59,18 @@ __global__ __launch_bounds__((NG == 1 ? kAttnWaves : kQaGemmWaves) * 64) void qk
     const int erow = eg * kGroupRows + em;
     const bool row_ok = em < kGroupRows && erow < a.rows;
     float inv_row = 1.0f;
-    if (a.ssq_in && w < GW) {
-        float sum = 0.f;
-        if (row_ok) {
-            const float *part = a.ssq_in + (size_t)erow * (KS * 2);
-            if ((a.ssq_in_parts & 3) == 0) {
-#pragma unroll 4
-                for (int p = en; p < (a.ssq_in_parts >> 2); p += 16) {
-                    const float4 q = reinterpret_cast<const float4 *>(part)[p];
-                    sum += (q.x + q.y) + (q.z + q.w);
-                }
-            } else {
-                for (int p = en; p < a.ssq_in_parts; p += 16) sum += part[p];
-            }
-        }
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-        inv_row = 1.0f / sqrtf(sum * (1.0f / (float)a.K) + a.eps);
-    }
+    if (a.ssq_in && w < GW)
+        inv_row = rms_inv_from_parts(a.ssq_in + (size_t)erow * (KS * 2), a.ssq_in_parts, en, row_ok, 1.0f / (float)a.K, a.eps);
 
 #pragma unroll
     for (int j = 0; j < 3; ++j) {
         const int t = tile0 + j * tstride;
         if (w < GW) {
             f32x4_t acc[NG];
-#pragma unroll
-            for (int g = 0; g < NG; ++g) acc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            const uint4 *wnext = (j < 2) ? W + ((size_t)(t + tstride) * KS + s0) * 64 : X;   // last tile: harmless re-read
-#pragma unroll
-            for (int i = 0; i < NB; ++i) {
-#pragma unroll
-                for (int g = 0; g < NG; ++g) acc[g] = qa_mfma(av[i % U], bv[g][i], acc[g]);
-                if (i + U < NB) av[i % U] = qa_load_stream(W + ((size_t)t * KS + s0 + i + U) * 64 + lane);
-                else av[i % U] = qa_load_stream(wnext + (size_t)(j < 2 ? (i + U - NB) : 0) * 64 + lane);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-#pragma unroll
-            for (int g = 0; g < NG; ++g)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float x = sum_terms(acc[g][v]);
-                    if ((lane & 15) < kGroupRows) red[j & 1][w][g][4 * (lane >> 4) + v][lane & 15] = x;
-                }
+            const uint4 *wcur = W + ((size_t)t * KS + s0) * 64 + lane;
+            const uint4 *wnext = ((j < 2) ? W + ((size_t)(t + tstride) * KS + s0) * 64 : X) + lane;   // last tile: harmless re-read
+            regb_tile<NB, U, NG>(acc, av, bv, wcur, wnext, j < 2);
+            store_partial<NG>(acc, red[j & 1][w], lane);
         }
         __syncthreads();
         if (w < GW && (w / (2 * NG)) == (j % (GW / (2 * NG))) && row_ok) {   // 2 NG waves finish tile j
@@ -114,18 +83,23 @@ __global__ __launch_bounds__((NG == 1 ? kAttnWaves : kQaGemmWaves) * 64) void qk
     // the slices are written through to memory; once acknowledged, count this workgroup in
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (threadIdx.x == 0) __hip_atomic_fetch_add(a.head_count + hh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // thread 0's ticket: counter value before this workgroup's arrival
+    unsigned ticket = 0;
+    if (threadIdx.x == 0) ticket = __hip_atomic_fetch_add(a.head_count + hh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
     // ---- attention of (head, slice) ------------------------------------------------------------
-    const unsigned target = a.count_before + (unsigned)S;
     auto wait_head = [&] {
-        if (threadIdx.x == 0 && __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
-            unsigned spins = 0;
-            while ((int)(__hip_atomic_load(a.head_count + hh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-                __builtin_amdgcn_s_sleep(1);
-                if (++spins > (1u << 22)) {                 // never in a healthy run: let everything drain
-                    __hip_atomic_store(a.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
+        if (threadIdx.x == 0) {
+            const unsigned target = (ticket / (unsigned)S + 1u) * (unsigned)S;     // this launch completes the head here
+            // the last of the head's S workgroups to arrive need not look at the counter at all
+            if (ticket + 1u != target && __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+                unsigned spins = 0;
+                while ((int)(__hip_atomic_load(a.head_count + hh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+                    __builtin_amdgcn_s_sleep(1);
+                    if (++spins > a.spin_limit) {               // never in a healthy run: let everything drain
+                        __hip_atomic_store(a.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
                 }
             }
         }

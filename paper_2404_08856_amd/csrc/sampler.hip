@@ -250,13 +250,15 @@ __device__ int sample_inverse_cdf_regs(WF wf, int V, float u, unsigned long long
         const unsigned long long excl = inc - v0 - v1;
         tmp[a0] = excl;
         tmp[a1] = excl + v0;
-        if (lane == 63) { tmp[16] = inc; *result = -1; }      // slot 16 of slice 0 is free: the grand total
+        // slot 16 of slices 0 and 1 is free: the grand total, and a zero that nobody rewrites before every
+        // thread has passed the barrier at the end of this function (the run-time zero `salt` below)
+        if (lane == 63) { tmp[16] = inc; tmp[17 + 16] = 0ull; *result = -1; }
     }
     __syncthreads();
     const unsigned long long S = tmp[16];
     if (S != 0) {
         const unsigned long long thr = threshold_of(u, S);
-        const unsigned long long salt = (unsigned long long)(*result + 1);   // result is -1 here
+        const unsigned long long salt = tmp[17 + 16];         // 0; read from memory that the matching thread below does not write
 #pragma unroll
         for (int i = 0; i < kRowVec; ++i) {
             const unsigned long long part = part_of(i, salt);

@@ -25,9 +25,10 @@ SPD_MAX_ROWS, SPD_MAX_M = 64, 8
 EXPORTS = ["spd_last_error", "spd_model_bytes", "spd_model_create", "spd_model_destroy", "spd_kv_set_len",
            "spd_kv_get_len", "spd_prefill", "spd_prefill_tokens", "spd_verify_forward", "spd_draft_step",
            "spd_accept_workspace_bytes", "spd_speculative_accept", "spd_trace_enable", "spd_trace_read",
-           "spd_trace_stages", "spd_kv_lens_to_device", "spd_kv_lens_from_device", "spd_draft_step_strided",
+           "spd_model_set_tuning", "spd_kv_lens_to_device", "spd_kv_lens_from_device", "spd_draft_step_strided",
            "spd_block_finish", "spd_device_status"]
-TRACE_KINDS = ["qkv", "o", "gate_up", "down", "lm_head", "attention", "forward", "embed"]
+TRACE_KINDS = ["qkv", "o", "gate_up", "down", "lm_head", "attention", "embed"]
+PROJECTIONS = ["qkv", "o", "gate_up", "down", "lm_head"]
 
 
 class SpdError(RuntimeError):
@@ -42,6 +43,12 @@ class spd_model_config(ctypes.Structure):
                 ("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float),
                 ("tied_embeddings", ctypes.c_int32), ("max_seqs", ctypes.c_int32),
                 ("max_positions", ctypes.c_int32)]
+
+
+class spd_tuning(ctypes.Structure):
+    _fields_ = [("separate_qkv_attention", ctypes.c_int32), ("attention_slices", ctypes.c_int32),
+                ("gemm_waves", ctypes.c_int32 * 5), ("gemm_grid_cap", ctypes.c_int32 * 5),
+                ("gemm_general_kernel", ctypes.c_int32 * 5), ("wait_spin_limit", ctypes.c_uint32)]
 
 
 _PP = ctypes.POINTER(ctypes.c_void_p)
@@ -61,6 +68,7 @@ _lib.spd_model_bytes.argtypes = [ctypes.POINTER(spd_model_config), _szp, _szp, _
 _lib.spd_model_create.argtypes = [ctypes.POINTER(spd_model_config), ctypes.POINTER(spd_weights), _vp, _sz, _vp, _sz,
                                   _vp, _sz, _vp, ctypes.POINTER(_vp)]
 _lib.spd_model_destroy.argtypes = [_vp]
+_lib.spd_model_set_tuning.argtypes = [_vp, ctypes.POINTER(spd_tuning)]
 _lib.spd_kv_set_len.argtypes = [_vp, ctypes.POINTER(_i32), _i32]
 _lib.spd_kv_get_len.argtypes = [_vp, ctypes.POINTER(_i32), _i32]
 _lib.spd_prefill.argtypes = [_vp, _i32, _vp, _i32, _vp, _vp]
@@ -71,7 +79,6 @@ _lib.spd_accept_workspace_bytes.argtypes = [_i32, _i32, _i32, _szp]
 _lib.spd_speculative_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _u32, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.spd_trace_enable.argtypes = [_vp, _i32]
 _lib.spd_trace_read.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i32)]
-_lib.spd_trace_stages.argtypes = [_vp, _i32] + [ctypes.POINTER(ctypes.c_double)] * 4 + [ctypes.POINTER(_i32)]
 _lib.spd_kv_lens_to_device.argtypes = [_vp, _vp]
 _lib.spd_kv_lens_from_device.argtypes = [_vp, _vp]
 _lib.spd_device_status.argtypes = [_vp, _vp]
@@ -162,6 +169,16 @@ class Model:
         self.close()
 
     # --- thin wrappers, same names as the C entry points ---------------------------------
+    def spd_model_set_tuning(self, separate_qkv_attention=0, attention_slices=0, gemm_waves=None, gemm_grid_cap=None,
+                             gemm_general_kernel=None, wait_spin_limit=0):
+        """Kernel-selection knobs for tests and sweeps; the per-projection dicts are keyed by PROJECTIONS."""
+        t = spd_tuning()
+        t.separate_qkv_attention, t.attention_slices, t.wait_spin_limit = int(separate_qkv_attention), int(attention_slices), int(wait_spin_limit)
+        for field, given in (("gemm_waves", gemm_waves), ("gemm_grid_cap", gemm_grid_cap), ("gemm_general_kernel", gemm_general_kernel)):
+            for name, value in (given or {}).items():
+                getattr(t, field)[PROJECTIONS.index(name)] = int(value)
+        _check(_lib.spd_model_set_tuning(self.handle, ctypes.byref(t)))
+
     def spd_kv_set_len(self, lens):
         a = (ctypes.c_int32 * len(lens))(*[int(x) for x in lens])
         _check(_lib.spd_kv_set_len(self.handle, a, len(lens)))
@@ -213,14 +230,6 @@ class Model:
 
     def spd_trace_enable(self, enable):
         _check(_lib.spd_trace_enable(self.handle, int(bool(enable))))
-
-    def spd_trace_stages(self, max_stages=4096):
-        """[(first arrival, last arrival, first departure, last departure)] in us per device-wide barrier
-        of the last traced whole-forward kernel."""
-        arr = [(ctypes.c_double * max_stages)() for _ in range(4)]
-        n = ctypes.c_int32()
-        _check(_lib.spd_trace_stages(self.handle, max_stages, *arr, ctypes.byref(n)))
-        return [tuple(a[i] for a in arr) for i in range(n.value)]
 
     def spd_trace_read(self):
         """{kind: (milliseconds summed over launches, launches)} since the last read; waits for the events."""

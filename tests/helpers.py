@@ -41,3 +41,35 @@ def check_logits(got, want, what=""):
     assert err.max() <= LOGIT_MAX_ABS and err.mean() <= LOGIT_MEAN_ABS, \
         f"{what}: max-abs {err.max():.3e} (limit {LOGIT_MAX_ABS}), mean-abs {err.mean():.3e} (limit {LOGIT_MEAN_ABS})"
     return err.max(), err.mean()
+
+
+def accept_margins(T_rows, D_rows, d_tokens, u):
+    """Relative distance of every accept test u * D(d) < T(d) from equality: a decision may differ between two
+    float paths only where this is tiny."""
+    return [abs(float(u[j]) * float(D_rows[j, d_tokens[j]]) - float(T_rows[j, d_tokens[j]])) /
+            max(float(T_rows[j, d_tokens[j]]), 1e-30) for j in range(len(d_tokens))]
+
+
+def drawn_token_is_valid(T_rows, D_rows, k, u_last, y, tol=1e-4):
+    """Is y what the fixed-point inverse-CDF sampler draws from row k's residual (bonus row for k = gamma),
+    up to a perturbation of the cumulative sums by tol * (total mass)?  With tol = 0 this is y == the oracle's
+    token.  Two softmax implementations that agree to ~1e-6 move the cumulative sums by that much, so the
+    drawn token may differ only when the threshold sits that close to a bucket boundary."""
+    from oracle import spec_sampling as ss
+    gamma = D_rows.shape[0]
+    r = ss.residual(T_rows[k], D_rows[k]) if k < gamma else np.asarray(T_rows[gamma], dtype=np.float32)
+    w = ss.fixed_point_weights(r)
+    S = int(np.sum(w, dtype=np.uint64))
+    if S == 0:
+        r = np.asarray(T_rows[min(k, gamma)], dtype=np.float32)
+        w = ss.fixed_point_weights(r)
+        S = int(np.sum(w, dtype=np.uint64))
+        if S == 0:
+            return y == 0
+    k_u = int(np.float64(np.float32(u_last)) * float(1 << 24))
+    thr = (k_u * S) >> 24
+    run = np.cumsum(w, dtype=np.uint64)
+    lo = int(run[y - 1]) if y > 0 else 0            # bucket of y: [lo, hi)
+    hi = int(run[y])
+    slack = int(tol * S)
+    return hi > lo and lo <= thr + slack and thr < hi + slack

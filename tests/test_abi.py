@@ -87,6 +87,14 @@ def test_product_does_not_import_the_oracle():
     assert len(uses) == 1 and "def cpu_baseline" in bench[:uses[0]] and "def side_configs" not in bench[:uses[0]]
 
 
+def test_product_reads_no_environment_variables():
+    """Kernel selection is fixed at model creation or set through spd_model_set_tuning: no hidden knobs."""
+    csrc = os.path.join(ROOT, "paper_2404_08856_amd", "csrc")
+    for name in os.listdir(csrc):
+        if name.endswith((".hip", ".h")):
+            assert "getenv" not in open(os.path.join(csrc, name)).read(), name
+
+
 def test_null_handles_are_refused_by_every_entry_point():
     """Host-side argument validation: a NULL model (or buffer) is an error code and a message, never a crash."""
     from paper_2404_08856_amd import spd
@@ -109,7 +117,7 @@ def test_null_handles_are_refused_by_every_entry_point():
         "spd_block_finish": (null, null, null, null, null, null, i32(1), i32(4), f32(1.0), null, null, null, null, i32(0), null, null, sz(0), null),
         "spd_trace_enable": (null, i32(1)),
         "spd_trace_read": (null, i32(8), null, null),
-        "spd_trace_stages": (null, i32(8), null, null, null, null, null),
+        "spd_model_set_tuning": (null, null),
     }
     for name, args in calls.items():
         fn = getattr(lib, name)

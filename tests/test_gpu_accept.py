@@ -11,6 +11,7 @@ import torch
 
 from oracle import spec_sampling as ss
 from paper_2404_08856_amd import synth
+from tests.helpers import accept_margins, drawn_token_is_valid
 
 pytestmark = pytest.mark.gpu
 
@@ -73,13 +74,14 @@ def test_accept_logits_mode_matches_up_to_near_ties():
         ks, ys = ss.speculative_accept(T[s], D[s], d[s], u[s])
         if (int(k[s]), int(y[s])) != (ks, ys):
             mismatches += 1
-            # only legitimate at a near-tie: of an accept test (k differs), or of the inverse-CDF
-            # threshold (same k, the neighbouring token of the cumulative sum)
-            margins = [abs(float(u[s, j]) * float(D[s, j, d[s, j]]) - float(T[s, j, d[s, j]])) /
-                       max(float(T[s, j, d[s, j]]), 1e-30) for j in range(gamma)]
-            if int(k[s]) != ks:
-                assert min(margins) < 1e-4, (s, margins)
-    assert mismatches <= 2, mismatches
+        # a decision may differ from the oracle's only at a near-tie: of an accept test (k differs), or of the
+        # inverse-CDF threshold (same k, a neighbouring bucket of the cumulative sum)
+        if int(k[s]) != ks:
+            assert min(accept_margins(T[s], D[s], d[s], u[s])) < 1e-4, s
+        # whatever k the device found, its token must be a valid draw from that row's residual / bonus row
+        assert drawn_token_is_valid(T[s], D[s], int(k[s]), u[s, gamma], int(y[s])), (s, int(k[s]), int(y[s]), ks, ys)
+    print("logits mode: sequences that differ from the oracle (near-ties):", mismatches)
+    assert mismatches <= n_seqs // 8
     ap_ref = np.array([[ss.accept_probability(T[s, j, d[s, j]], D[s, j, d[s, j]]) for j in range(gamma)]
                        for s in range(n_seqs)])
     assert np.max(np.abs(ap - ap_ref)) < 1e-4
@@ -95,9 +97,11 @@ def test_accept_mixed_mode_target_logits_draft_probs_and_temperature():
     d = draw_draft_tokens(D, synth.uniforms((n_seqs, gamma), 8))
     u = synth.uniforms((n_seqs, gamma + 1), 9)
     k, y, ap = run_accept(lt, D, d, u, temp, spd.SPD_DRAFT_IS_PROBS)
-    want = [ss.speculative_accept(T[s], D[s], d[s], u[s]) for s in range(n_seqs)]
-    agree = sum((int(a), int(b)) == w for a, b, w in zip(k, y, want))
-    assert agree >= n_seqs - 1
+    for s in range(n_seqs):
+        ks, ys = ss.speculative_accept(T[s], D[s], d[s], u[s])
+        if int(k[s]) != ks:
+            assert min(accept_margins(T[s], D[s], d[s], u[s])) < 1e-4, s
+        assert drawn_token_is_valid(T[s], D[s], int(k[s]), u[s, gamma], int(y[s])), s
     ap_ref = np.array([[ss.accept_probability(T[s, j, d[s, j]], D[s, j, d[s, j]]) for j in range(gamma)]
                        for s in range(n_seqs)])
     assert np.max(np.abs(ap - ap_ref)) < 1e-4

@@ -112,6 +112,50 @@ def test_draft_shape_sequential_steps():
     model.close()
 
 
+def test_paper_draft_shape_prefill_steps_and_verify_shaped_call():
+    """The paper's own draft (Appendix A.1, Table 1: 4 layers, hidden 1024, 8 heads of 128, intermediate
+    2816, untied 32000-entry head): 64-token prefill, 4 sequential single-token steps with sampling, then one
+    5-token call (the shape a verify step has), all against the oracle."""
+    from oracle import spec_sampling as ss
+    shape = synth.SHAPES["draft_paper_115m"]
+    print("case paper draft shape", flush=True)
+    model, wn = build_pair(shape, 13, 1, 128)
+    cfg = oracle_cfg(shape)
+    toks = synth.text_tokens(64, shape.vocab, 13)
+    cache = dec.KVCache(cfg, 128)
+    ref_last = dec.forward_tokens(cfg, wn, cache, toks[:-1])[-1]
+    last = torch.empty(shape.vocab, dtype=torch.float32, device="cuda")
+    model.spd_prefill_tokens(0, torch.from_numpy(toks[:-1]).cuda(), last)
+    check_logits(last.cpu().numpy(), ref_last, "prefill")
+    u = synth.uniforms((4,), 14)
+    t = int(toks[-1])
+    D = torch.empty((1, shape.vocab), dtype=torch.float32, device="cuda")
+    tok = torch.empty((1,), dtype=torch.int32, device="cuda")
+    for j in range(4):
+        ref_logits = dec.forward_tokens(cfg, wn, cache, [t])[0]
+        model.spd_draft_step(torch.tensor([[t]], dtype=torch.int32, device="cuda"), 1.0,
+                             torch.from_numpy(u[j:j + 1]).cuda(), D, tok)
+        D_gpu = D.cpu().numpy()[0]
+        D_ref = ss.softmax_probs(ref_logits, 1.0)
+        assert abs(D_gpu.sum() - 1.0) < 1e-4
+        assert np.max(np.abs(np.log(D_gpu.astype(np.float64)) - np.log(D_ref.astype(np.float64)))) < 2 * 3e-2
+        assert int(tok.item()) == ss.sample_row(D_gpu, u[j])
+        t = int(tok.item())
+    vt = synth.text_tokens(5, shape.vocab, 15)
+    ref = dec.forward_tokens(cfg, wn, cache, vt)
+    out = torch.empty((1, 5, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_verify_forward(torch.from_numpy(vt).cuda()[None].contiguous(), out)
+    mx, mean = check_logits(out.cpu().numpy()[0], ref, "5-token call")
+    print("paper draft shape 5-token call err", mx, mean)
+    # two-token step (after a fully accepted block)
+    ref2 = dec.forward_tokens(cfg, wn, cache, [3, 4])[-1]
+    model.spd_draft_step(torch.tensor([[3, 4]], dtype=torch.int32, device="cuda"), 1.0, torch.from_numpy(u[:1]).cuda(), D, tok)
+    D_gpu = D.cpu().numpy()[0]
+    assert np.max(np.abs(np.log(D_gpu.astype(np.float64)) - np.log(ss.softmax_probs(ref2, 1.0).astype(np.float64)))) < 2 * 3e-2
+    assert model.spd_kv_get_len(1) == [cache.length]
+    model.close()
+
+
 def test_multi_sequence_ragged_lengths_and_rollback():
     """3 sequences with different prefix lengths verified in one call; then a
     rollback (rejection) on each and a second call."""
@@ -185,19 +229,6 @@ def test_verify_is_deterministic_run_to_run():
     model.close()
 
 
-@pytest.mark.parametrize("case", ["tiny", "draft", "7b2"])
-def test_whole_forward_persistent_kernel_opt_in(case, monkeypatch):
-    """The single-launch persistent kernel for calls of up to 8 rows (opt-in through the
-    environment at model creation) computes the same forward."""
-    monkeypatch.setenv("SPD_MEGA", "1")
-    if case == "tiny":
-        run_case(synth.SHAPES["tiny_target"], 32, 32, 5, seed=31, extra_steps=1)
-    elif case == "draft":
-        run_case(synth.SHAPES["tiny_draft"], 0, 65, 1, seed=32, extra_steps=2)
-    else:
-        run_case(synth.llama7b_layers(2), 576, 64, 5, seed=33)
-
-
 @pytest.mark.timeout(900)
 def test_llama7b_full_depth_against_oracle_short_context():
     """All 32 layers of the 7B shape (every weight byte the benchmark streams) against the
@@ -229,6 +260,41 @@ def test_llama7b_full_depth_against_oracle_short_context():
     model.spd_verify_forward(torch.from_numpy(vt).cuda()[None].contiguous(), out)
     mx, mean = check_logits(out.cpu().numpy()[0], ref, "verify")
     print("full-depth 7B verify err", mx, mean)
+    model.close()
+
+
+@pytest.mark.timeout(1500)
+def test_llama7b_benchmark_point_against_oracle():
+    """The benchmarked configuration itself -- Table 1 target shape, all 32 layers, KV prefix of 576 image rows
+    + 64 text tokens, gamma + 1 = 5 tokens, the benchmark's seeds -- against the oracle.  One oracle pass over
+    all 645 rows gives the prefill's last row and the 5 verify rows (cached forward = full recompute, an
+    invariant the oracle is pinned by); the device runs the prefill in 40-row passes and then the 5-row step."""
+    shape = synth.SHAPES["llama7b"]
+    spd = spd_mod()
+    seed, m_img, n_text, M = 0, 576, 64, 5
+    print("case 7B benchmark point vs oracle", flush=True)
+    w = synth.make_weights(shape, seed, device="cuda")
+    model = spd.Model(spd.make_config(shape, 1, m_img + n_text + M + 3), w)
+    wn = synth.weights_to_numpy(w)
+    del w
+    torch.cuda.empty_cache()
+    img = synth.image_rows(m_img, shape.d_model, seed)
+    text = synth.text_tokens(n_text, shape.vocab, seed)
+    vt = synth.text_tokens(M, shape.vocab, seed + 1)
+    last = torch.empty(shape.vocab, dtype=torch.float32, device="cuda")
+    model.spd_prefill(0, torch.from_numpy(img).cuda())
+    model.spd_prefill_tokens(0, torch.from_numpy(text).cuda(), last)
+    out = torch.empty((1, M, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_verify_forward(torch.from_numpy(vt).cuda()[None].contiguous(), out)
+    torch.cuda.synchronize()
+    print("device done; oracle pass over 645 rows x 32 layers (float64) ...", flush=True)
+    cfg = oracle_cfg(shape)
+    x = np.concatenate([img.astype(np.float64), dec.embed_tokens(wn, text), dec.embed_tokens(wn, vt)])
+    ref = dec.full_recompute(cfg, wn, x)
+    print("oracle done", flush=True)
+    mx0, mean0 = check_logits(last.cpu().numpy(), ref[m_img + n_text - 1], "prefill last row")
+    mx, mean = check_logits(out.cpu().numpy()[0], ref[m_img + n_text:], "verify rows")
+    print(f"benchmark point: prefill last row max-abs {mx0:.3e} mean-abs {mean0:.3e}; verify max-abs {mx:.3e} mean-abs {mean:.3e}")
     model.close()
 
 
@@ -300,16 +366,16 @@ def test_batched_verify_many_row_groups(n_seqs, M):
 @pytest.mark.parametrize("dev_lens", [False, True])
 @pytest.mark.parametrize("fuse", [True, False])
 @pytest.mark.parametrize("M", [1, 5, 6, 8])
-def test_qkv_attention_fused_and_separate_kernels(fuse, M, dev_lens, monkeypatch):
+def test_qkv_attention_fused_and_separate_kernels(fuse, M, dev_lens):
     """d_model 4096 with 2 heads of 128: the shape class that takes the fused QKV + attention kernel
     (one workgroup per head and 16 output dimensions, per-head arrival counter), against the
     oracle, with the fusion on and off; several calls so that the counters advance."""
-    if not fuse:
-        monkeypatch.setenv("SPD_NO_FUSE", "1")
     shape = synth.ModelShape(2, 4096, 2, 128, 256, 1024)
     print(f"case fused={fuse} M={M}", flush=True)
     spd = spd_mod()
     model, wn = build_pair(shape, 51, 1, 128)
+    if not fuse:
+        model.spd_model_set_tuning(separate_qkv_attention=1)
     cfg = oracle_cfg(shape)
     cache = dec.KVCache(cfg, 128)
     toks = synth.text_tokens(70, shape.vocab, 51)
@@ -437,15 +503,14 @@ def test_batched_verify_wide_model(n_seqs, M):
 
 
 @pytest.mark.parametrize("slices", [1, 2, 4, 8])
-def test_attention_head_slicing_variants(slices, monkeypatch):
+def test_attention_head_slicing_variants(slices):
     """Every way of cutting a 128-wide head over workgroups (1, 2, 4 or 8 slices; chosen by batch
     size in production) gives the same attention: forced here on a 3-sequence batch with 7 rows each
     (two attention launches per layer) and on a single sequence without the fused kernel."""
-    monkeypatch.setenv("SPD_ATTN_SLICES", str(slices))
-    monkeypatch.setenv("SPD_NO_FUSE", "1")
     shape = synth.ModelShape(1, 4096, 2, 128, 256, 1024)
     print(f"case slices={slices}", flush=True)
     model, wn = build_pair(shape, 61, 3, 100)
+    model.spd_model_set_tuning(separate_qkv_attention=1, attention_slices=slices)
     cfg = oracle_cfg(shape)
     caches = []
     for s in range(3):
@@ -480,7 +545,6 @@ def test_tracing_counts_every_launch_group():
     counts = {k: n for k, (ms, n) in tr.items()}
     assert counts["qkv"] == 2 * L and counts["attention"] == 2 * L and counts["o"] == 2 * L
     assert counts["gate_up"] == 2 * L and counts["down"] == 2 * L and counts["lm_head"] == 2 and counts["embed"] == 2
-    assert counts["forward"] == 0
     assert all(ms > 0 for k, (ms, n) in tr.items() if n)
     assert all(n == 0 for ms, n in model.spd_trace_read().values())        # reading forgets
     model.spd_trace_enable(False)
@@ -496,7 +560,7 @@ def test_long_context_needs_several_key_iterations_per_wave(shape_name, prefix):
     run_case(synth.SHAPES[shape_name], 0, prefix, 5, seed=prefix % 97, extra_steps=1)
 
 
-def test_long_context_batch_with_unsliced_heads(monkeypatch):
+def test_long_context_batch_with_unsliced_heads():
     """Head dimension 128, several sequences at contexts of 900 to 1300 keys, every head slicing."""
     shape = synth.ModelShape(1, 4096, 2, 128, 256, 1024)
     model, wn = build_pair(shape, 83, 3, 1320)
@@ -509,7 +573,7 @@ def test_long_context_batch_with_unsliced_heads(monkeypatch):
         caches.append(c)
         model.spd_prefill_tokens(s, torch.from_numpy(toks).cuda())
     for slices in (1, 2, 8):
-        monkeypatch.setenv("SPD_ATTN_SLICES", str(slices))
+        model.spd_model_set_tuning(attention_slices=slices)
         vt = np.stack([synth.text_tokens(4, shape.vocab, 950 + 10 * slices + s) for s in range(3)])
         out = torch.empty((3, 4, shape.vocab), dtype=torch.float32, device="cuda")
         model.spd_verify_forward(torch.from_numpy(vt).cuda(), out)

@@ -4,10 +4,13 @@ both KV caches -- every step through the C ABI, with the host only sequencing th
 
 The oracle runs beside the device in lock step on the device's own token history (two
 float paths that agree to 3e-2 in the logits may still draw different tokens, after which
-the histories would no longer be comparable).  Per block it checks
+the histories would no longer be comparable).  The oracle side keeps NO cache: every
+reference row is a recompute from scratch over the true history (prompt, every token
+emitted so far, this block's drafted tokens before the row; the draft without the image
+rows), so a mistake in the rollback bookkeeping cannot be mirrored on both sides.  Per
+block it checks
 
-  * the draft rows D_j and the target logits against the oracle's forward on the same
-    history (spec tolerance),
+  * the draft rows D_j and the target logits against that recompute (spec tolerance),
   * every drafted token against the oracle's sampler applied to the device's own D_j with
     the same uniform (bit-exact),
   * (k, y) against the oracle's accept / resample on the same T, D, tokens and uniforms
@@ -21,7 +24,7 @@ import torch
 from oracle import decoder as dec
 from oracle import spec_sampling as ss
 from paper_2404_08856_amd import synth
-from tests.helpers import check_logits, oracle_cfg, randomize_gains, to_device
+from tests.helpers import accept_margins, check_logits, drawn_token_is_valid, oracle_cfg, randomize_gains, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -48,6 +51,30 @@ def make_pair(t_shape, d_shape, seed, cap, aligned, noise):
     return target, draft, synth.weights_to_numpy(tw), synth.weights_to_numpy(dw)
 
 
+def draft_row_ref(dc, dwn, history, temperature):
+    """D(. | history): the draft's distribution after the text-only history, recomputed from an empty cache."""
+    x = dec.embed_tokens(dwn, np.asarray(history, dtype=np.int64))
+    return dec.full_recompute(dc, dwn, x)[-1]
+
+
+def target_rows_ref(tc, twn, image, history, n_last):
+    """Target logits of the last n_last positions of [image rows ; E[history]], recomputed from an empty cache."""
+    x = dec.embed_tokens(twn, np.asarray(history, dtype=np.int64))
+    if image is not None:
+        x = np.concatenate([image.astype(np.float64), x])
+    return dec.full_recompute(tc, twn, x)[-n_last:]
+
+
+def check_draft_row(D_j, ref_logits, temperature):
+    D_ref = ss.softmax_probs(ref_logits, temperature)
+    if temperature > 0:
+        big = D_ref > 1e-12
+        assert np.max(np.abs(np.log(D_j[big].astype(np.float64)) - np.log(D_ref[big].astype(np.float64)))) < 2 * 3e-2 / temperature
+    else:                                                  # greedy: one-hot rows; the argmax may differ only at a near-tie
+        top = np.sort(ref_logits)[-2:]
+        assert D_j.sum() == 1.0 and (int(np.argmax(D_j)) == int(np.argmax(ref_logits)) or top[1] - top[0] < 6e-2)
+
+
 def run_loop(t_shape, d_shape, m_img, n_text, gamma, n_blocks, temperature, seed, aligned, noise=0.02):
     spd = spd_mod()
     cap = m_img + n_text + n_blocks * (gamma + 1) + 8
@@ -55,14 +82,12 @@ def run_loop(t_shape, d_shape, m_img, n_text, gamma, n_blocks, temperature, seed
     tc, dc = oracle_cfg(t_shape), oracle_cfg(d_shape)
     V = t_shape.vocab
     toks = synth.text_tokens(n_text, V, seed)
-    t_cache, d_cache = dec.KVCache(tc, cap), dec.KVCache(dc, cap)
+    image = None if m_img == 0 else synth.image_rows(m_img, t_shape.d_model, seed)
 
     # prefill: target sees [image rows ; text], the draft the text alone (Section 3)
     x_text = dec.embed_tokens(twn, toks)
-    x = x_text if m_img == 0 else np.concatenate(
-        [synth.image_rows(m_img, t_shape.d_model, seed).astype(np.float64), x_text])
-    ref_last = dec.forward_rows(tc, twn, t_cache, x)[-1]
-    dec.forward_tokens(dc, dwn, d_cache, toks)
+    x = x_text if m_img == 0 else np.concatenate([image.astype(np.float64), x_text])
+    ref_last = target_rows_ref(tc, twn, image, toks, 1)[0]
     last = torch.empty(V, dtype=torch.float32, device="cuda")
     target.spd_prefill(0, torch.from_numpy(x.astype(np.float32)).cuda(), last)
     draft.spd_prefill_tokens(0, torch.from_numpy(toks).cuda())
@@ -80,26 +105,22 @@ def run_loop(t_shape, d_shape, m_img, n_text, gamma, n_blocks, temperature, seed
     y_dev = torch.empty((1,), dtype=torch.int32, device="cuda")
     pending = [t]
     out, ks = [t], []
+    history = [int(x) for x in toks]                       # text prompt + every emitted token before t
     for b in range(n_blocks):
         print(f"loop block {b} t={t} pending={pending}", flush=True)
         d_tokens = []
         for j in range(gamma):
-            ref = dec.forward_tokens(dc, dwn, d_cache, pending)[-1]
+            ref = draft_row_ref(dc, dwn, history + [t] + d_tokens, temperature)
             draft.spd_draft_step(torch.tensor([pending], dtype=torch.int32, device="cuda"), temperature,
                                  torch.from_numpy(u_draft[b, j:j + 1]).cuda(), D_dev[:, j], tok_dev)
             D_j = D_dev[0, j].cpu().numpy()
-            D_ref = ss.softmax_probs(ref, temperature)
-            if temperature > 0:
-                big = D_ref > 1e-12
-                assert np.max(np.abs(np.log(D_j[big].astype(np.float64)) - np.log(D_ref[big].astype(np.float64)))) \
-                    < 2 * 3e-2 / temperature
+            check_draft_row(D_j, ref, temperature)
             d_j = int(tok_dev.item())
             assert d_j == ss.sample_row(D_j, u_draft[b, j]), (b, j)
             d_tokens.append(d_j)
             pending = [d_j]
-        P = t_cache.length
         block = [t] + d_tokens
-        ref_t = dec.forward_tokens(tc, twn, t_cache, block)
+        ref_t = target_rows_ref(tc, twn, image, history + block, gamma + 1)
         target.spd_verify_forward(torch.tensor([block], dtype=torch.int32, device="cuda"), logits_dev)
         lg = logits_dev[0].cpu().numpy()
         check_logits(lg, ref_t, f"verify block {b}")
@@ -118,17 +139,17 @@ def run_loop(t_shape, d_shape, m_img, n_text, gamma, n_blocks, temperature, seed
         spd.spd_speculative_accept(logits_dev, D_dev, torch.tensor([d_tokens], dtype=torch.int32, device="cuda"),
                                    torch.from_numpy(u_accept[b:b + 1]).cuda(), temperature,
                                    spd.SPD_DRAFT_IS_PROBS, k2, y2)
-        margins = [abs(float(u_accept[b, j]) * float(D_rows[j, d_tokens[j]]) - float(T_rows[j, d_tokens[j]])) /
-                   max(float(T_rows[j, d_tokens[j]]), 1e-30) for j in range(gamma)]
-        if min(margins) > 1e-3:
+        if min(accept_margins(T_rows, D_rows, d_tokens, u_accept[b])) > 1e-3:
             assert int(k2.item()) == k, b
-        # rollback: target keeps t, d_1..d_k; draft keeps t, d_1..d_min(k, gamma-1)
-        t_cache.truncate(P + k + 1)
-        target.spd_kv_set_len([P + k + 1])
-        d_len = d_cache.length - (gamma - 1) + min(k, gamma - 1)
-        d_cache.truncate(d_len)
+        assert drawn_token_is_valid(T_rows, D_rows, int(k2.item()), u_accept[b, gamma], int(y2.item())), b
+        # rollback: target keeps t, d_1..d_k; draft keeps t, d_1..d_min(k, gamma-1).  Expected lengths follow
+        # from the history alone: the target holds image + everything before y, the draft the text before y
+        # minus the drafted token it has not consumed yet after a full acceptance
+        history = history + [t] + d_tokens[:k]
+        t_len = m_img + len(history)
+        d_len = len(history) - (1 if k == gamma else 0)
+        target.spd_kv_set_len([t_len])
         draft.spd_kv_set_len([d_len])
-        assert target.spd_kv_get_len(1) == [t_cache.length] and draft.spd_kv_get_len(1) == [d_cache.length]
         pending = [d_tokens[gamma - 1], y] if k == gamma else [y]
         out.extend(d_tokens[:k])
         out.append(y)
@@ -235,65 +256,63 @@ def setup_device_loop(n_seqs, gamma, n_blocks, temperature, seed, m_img):
     for s in range(n_seqs):
         n_text = 12 + 9 * s
         toks = synth.text_tokens(n_text, V, seed + s)
-        x = np.concatenate([synth.image_rows(m_img, t_shape.d_model, seed + s).astype(np.float64), dec.embed_tokens(twn, toks)])
-        t_cache, d_cache = dec.KVCache(tc, cap), dec.KVCache(dc, cap)
-        ref_last = dec.forward_rows(tc, twn, t_cache, x)[-1]
-        dec.forward_tokens(dc, dwn, d_cache, toks)
+        image = synth.image_rows(m_img, t_shape.d_model, seed + s)
+        x = np.concatenate([image.astype(np.float64), dec.embed_tokens(twn, toks)])
+        ref_last = target_rows_ref(tc, twn, image, toks, 1)[0]
         last = torch.empty(V, dtype=torch.float32, device="cuda")
         target.spd_prefill(s, torch.from_numpy(x.astype(np.float32)).cuda(), last)
         draft.spd_prefill_tokens(s, torch.from_numpy(toks).cuda())
         check_logits(last.cpu().numpy(), ref_last, f"prefill seq {s}")
         t = ss.sample_row(ss.softmax_probs(last.cpu().numpy(), temperature), u_first[s])
-        # loop convention: the draft's cache ends before the token that precedes t
-        d_cache.truncate(n_text - 1)
-        oracle.append(dict(t_cache=t_cache, d_cache=d_cache, prev=int(toks[-1]), t=t, out=[]))
+        # history = text prompt + every emitted token before t (the oracle side keeps no cache)
+        oracle.append(dict(image=image, history=[int(v) for v in toks], t=t, out=[]))
         loop.vt[s, 0] = t
         loop.din[s, 0] = int(toks[-1])
         loop.din[s, 1] = t
-    draft.spd_kv_set_len([o["d_cache"].length for o in oracle])
+    # loop convention: the draft's cache ends before the token that precedes t
+    draft.spd_kv_set_len([len(o["history"]) - 1 for o in oracle])
     target.spd_kv_lens_to_device()
     draft.spd_kv_lens_to_device()
-    return loop, oracle, (tc, twn, dc, dwn)
+    return loop, oracle, (tc, twn, dc, dwn, m_img)
+
+
+def expected_lengths(oracle, m_img):
+    """KV lengths the loop convention implies for the current histories: the target holds image + everything
+    before t, the draft the text before the token that precedes t."""
+    return [m_img + len(o["history"]) for o in oracle], [len(o["history"]) - 1 for o in oracle]
 
 
 def check_block_against_oracle(loop, oracle, models, u_draft_b, u_accept_b, b):
-    tc, twn, dc, dwn = models
+    tc, twn, dc, dwn, m_img = models
     g, temperature = loop.gamma, loop.temperature
     D_all, lg_all = loop.D.cpu().numpy(), loop.logits.cpu().numpy()
     k_all, y_all = loop.k.cpu().numpy(), loop.y.cpu().numpy()
     ks = []
     for s, o in enumerate(oracle):
-        pending, d_tokens = [o["prev"], o["t"]], []
+        d_tokens = []
         for j in range(g):
-            ref = dec.forward_tokens(dc, dwn, o["d_cache"], pending)[-1]
-            D_ref = ss.softmax_probs(ref, temperature)
+            ref = draft_row_ref(dc, dwn, o["history"] + [o["t"]] + d_tokens, temperature)
             D_j = D_all[s, j]
-            if temperature > 0:
-                big = D_ref > 1e-12
-                assert np.max(np.abs(np.log(D_j[big].astype(np.float64)) - np.log(D_ref[big].astype(np.float64)))) < 2 * 3e-2 / temperature
-            else:                                              # greedy: one-hot rows; the argmax may differ only at a near-tie
-                top = np.sort(ref)[-2:]
-                assert D_j.sum() == 1.0 and (int(np.argmax(D_j)) == int(np.argmax(ref)) or top[1] - top[0] < 6e-2)
+            check_draft_row(D_j, ref, temperature)
             d_j = ss.sample_row(D_j, u_draft_b[s, j])          # the device must have drawn exactly this token
             d_tokens.append(d_j)
-            pending = [d_j]
-        P = o["t_cache"].length
-        ref_t = dec.forward_tokens(tc, twn, o["t_cache"], [o["t"]] + d_tokens)
+        ref_t = target_rows_ref(tc, twn, o["image"], o["history"] + [o["t"]] + d_tokens, g + 1)
         check_logits(lg_all[s], ref_t, f"block {b} seq {s}")
         # the product decides on its own float32 softmax of the logits; the oracle's float64 softmax of the
         # same logits may differ at near-ties only
         T_rows = ss.softmax_probs(lg_all[s], temperature)
         k_ref, y_ref = ss.speculative_accept(T_rows, D_all[s], d_tokens, u_accept_b[s])
         k, y = int(k_all[s]), int(y_all[s])
-        margins = [abs(float(u_accept_b[s, j]) * float(D_all[s, j, d_tokens[j]]) - float(T_rows[j, d_tokens[j]])) /
-                   max(float(T_rows[j, d_tokens[j]]), 1e-30) for j in range(g)]
-        if min(margins) > 1e-3:
+        if min(accept_margins(T_rows, D_all[s], d_tokens, u_accept_b[s])) > 1e-3:
             assert k == k_ref, (b, s, k, k_ref)
+        if temperature > 0:
+            assert drawn_token_is_valid(T_rows, D_all[s], k, u_accept_b[s, g], y), (b, s, k, y, k_ref, y_ref)
+        else:                                              # greedy: y = argmax of the target row, up to a near-tie of the logits
+            top = np.sort(lg_all[s][k])[-2:]
+            assert y == int(np.argmax(lg_all[s][k])) or top[1] - top[0] < 1e-5, (b, s, k, y)
         emitted = d_tokens[:k] + [y]
         o["out"].extend(emitted)
-        o["t_cache"].truncate(P + k + 1)
-        o["d_cache"].truncate(o["d_cache"].length - (g - k))
-        o["prev"] = d_tokens[k - 1] if k >= 1 else o["t"]
+        o["history"] = o["history"] + [o["t"]] + d_tokens[:k]
         o["t"] = y
         ks.append(k)
     return ks
@@ -316,8 +335,9 @@ def test_device_block_loop_lockstep(n_seqs, gamma, temperature):
     print("accepted per block", all_ks)
     loop.target.spd_kv_lens_from_device()
     loop.draft.spd_kv_lens_from_device()
-    assert loop.target.spd_kv_get_len(n_seqs) == [o["t_cache"].length for o in oracle]
-    assert loop.draft.spd_kv_get_len(n_seqs) == [o["d_cache"].length for o in oracle]
+    t_lens, d_lens = expected_lengths(oracle, 16)
+    assert loop.target.spd_kv_get_len(n_seqs) == t_lens
+    assert loop.draft.spd_kv_get_len(n_seqs) == d_lens
     n_out = loop.n_out.cpu().numpy()
     out = loop.out.cpu().numpy()
     for s, o in enumerate(oracle):
@@ -347,8 +367,9 @@ def test_device_block_loop_as_graph_replays_equal_eager():
             torch.cuda.synchronize()
             loop.target.spd_kv_lens_from_device()
             loop.draft.spd_kv_lens_from_device()
-            loop.target.spd_kv_set_len([o["t_cache"].length for o in oracle])
-            loop.draft.spd_kv_set_len([o["d_cache"].length for o in oracle])
+            t_lens, d_lens = expected_lengths(oracle, 8)
+            loop.target.spd_kv_set_len(t_lens)
+            loop.draft.spd_kv_set_len(d_lens)
             loop.target.spd_kv_lens_to_device()
             loop.draft.spd_kv_lens_to_device()
             for t, sv in zip((loop.vt, loop.din, loop.out, loop.n_out), saved):
