@@ -203,6 +203,20 @@ int32_t spd_speculative_accept(const float *target, const float *draft, const in
                                int32_t *next_token_out, float *accept_prob_out,
                                void *workspace, size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): spd_speculative_accept with its scratch memory in
+ * a fixed 64 KiB array inside the library (one copy per GPU, held until the process ends).  Same
+ * arguments, results and errors as spd_speculative_accept, minus the workspace; calls nothing that
+ * allocates.  Limit: n_seqs * (2 gamma + 1) <= SPD_STATIC_ACCEPT_MAX_ROWS, else SPD_ERR_CAPACITY and
+ * nothing is launched.  All calls on one GPU share that GPU's array: calls that may overlap (different
+ * streams, different threads) race on it -- order them, or use spd_speculative_accept with one
+ * workspace per stream.  Nothing in the array has to survive between calls. */
+#define SPD_STATIC_ACCEPT_MAX_ROWS 4096
+int32_t spd_speculative_accept_static(const float *target, const float *draft, const int32_t *draft_tokens,
+                                      const float *u, int32_t n_seqs, int32_t gamma, int32_t vocab,
+                                      float temperature, uint32_t flags, int32_t *n_accepted_out,
+                                      int32_t *next_token_out, float *accept_prob_out, void *stream);
+
 /* ---- the block loop without the host (Section 2.1, one block = gamma draft steps, one
  * target call, accept / resample, commit) ---------------------------------------------
  *

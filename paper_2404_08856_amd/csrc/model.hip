@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -603,6 +604,62 @@ int32_t spd_speculative_accept(const float *target, const float *draft, const in
     a.n_accepted = n_accepted_out; a.next_token = next_token_out; a.accept_prob = accept_prob_out;
     a.token_stride = gamma;
     a.stats = (float *)workspace;
+    HIP_TRY(launch_accept(a, (hipStream_t)stream));
+    return SPD_OK;
+}
+
+}  // extern "C"
+
+// ---- accept / resample for callers that cannot allocate ----------------------------------------
+// The row statistics that spd_speculative_accept keeps in a caller-provided workspace live here in a
+// fixed array in device memory.  Every GPU the library runs on holds its own copy at its own address;
+// in host code the array's name is only a stand-in for it, so the address is looked up once per
+// device (with that device current) and only that pointer is ever handed to a kernel.
+namespace {
+constexpr size_t kStaticAcceptBytes = 64 * 1024;          // 4096 rows of statistics
+static __device__ __align__(256) unsigned char scratch[kStaticAcceptBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int32_t static_scratch(void **out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(SPD_ERR_HIP, "device index %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(SPD_ERR_HIP, "hipGetSymbolAddress returned a NULL address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SPD_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int32_t spd_speculative_accept_static(const float *target, const float *draft, const int32_t *draft_tokens, const float *u,
+                                      int32_t n_seqs, int32_t gamma, int32_t vocab, float temperature, uint32_t flags,
+                                      int32_t *n_accepted_out, int32_t *next_token_out, float *accept_prob_out, void *stream) {
+    if (!target || !draft || !draft_tokens || !u || !n_accepted_out || !next_token_out)
+        return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_speculative_accept_static");
+    if (n_seqs < 1 || gamma < 1 || gamma > 63 || vocab < 1) return fail(SPD_ERR_INVALID_ARG, "n_seqs, vocab >= 1 and 1 <= gamma <= 63 required");
+    if (!(temperature >= 0.f)) return fail(SPD_ERR_INVALID_ARG, "temperature must be >= 0");
+    if (flags & ~3u) return fail(SPD_ERR_INVALID_ARG, "unknown flag bits");
+    if ((size_t)n_seqs > SPD_STATIC_ACCEPT_MAX_ROWS || accept_workspace_bytes(n_seqs, gamma) > kStaticAcceptBytes)
+        return fail(SPD_ERR_CAPACITY, "n_seqs * (2 gamma + 1) = %lld rows exceed the %d rows of the built-in scratch array",
+                    (long long)n_seqs * (2 * gamma + 1), SPD_STATIC_ACCEPT_MAX_ROWS);
+    void *ws = nullptr;
+    int32_t rc = static_scratch(&ws);
+    if (rc) return rc;
+    AcceptArgs a;
+    a.target = target; a.draft = draft; a.draft_tokens = draft_tokens; a.u = u;
+    a.n_seqs = n_seqs; a.gamma = gamma; a.vocab = vocab; a.temperature = temperature; a.flags = flags;
+    a.n_accepted = n_accepted_out; a.next_token = next_token_out; a.accept_prob = accept_prob_out;
+    a.token_stride = gamma;
+    a.stats = (float *)ws;            // every entry the kernels read is written by this call first: nothing to clear
     HIP_TRY(launch_accept(a, (hipStream_t)stream));
     return SPD_OK;
 }

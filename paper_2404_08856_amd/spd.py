@@ -26,7 +26,7 @@ EXPORTS = ["spd_last_error", "spd_model_bytes", "spd_model_create", "spd_model_d
            "spd_kv_get_len", "spd_prefill", "spd_prefill_tokens", "spd_verify_forward", "spd_draft_step",
            "spd_accept_workspace_bytes", "spd_speculative_accept", "spd_trace_enable", "spd_trace_read",
            "spd_model_set_tuning", "spd_kv_lens_to_device", "spd_kv_lens_from_device", "spd_draft_step_strided",
-           "spd_block_finish", "spd_device_status"]
+           "spd_block_finish", "spd_device_status", "spd_speculative_accept_static"]
 TRACE_KINDS = ["qkv", "o", "gate_up", "down", "lm_head", "attention", "embed"]
 PROJECTIONS = ["qkv", "o", "gate_up", "down", "lm_head"]
 
@@ -77,6 +77,7 @@ _lib.spd_verify_forward.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp]
 _lib.spd_draft_step.argtypes = [_vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp, _vp]
 _lib.spd_accept_workspace_bytes.argtypes = [_i32, _i32, _i32, _szp]
 _lib.spd_speculative_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _u32, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.spd_speculative_accept_static.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _u32, _vp, _vp, _vp, _vp]
 _lib.spd_trace_enable.argtypes = [_vp, _i32]
 _lib.spd_trace_read.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i32)]
 _lib.spd_kv_lens_to_device.argtypes = [_vp, _vp]
@@ -275,3 +276,15 @@ def spd_speculative_accept(target, draft, draft_tokens, u, temperature, flags, n
                                        float(temperature), int(flags), _ptr(n_accepted_out, torch.int32),
                                        _ptr(next_token_out, torch.int32), _ptr(accept_prob_out, torch.float32),
                                        _ptr(workspace), workspace.numel(), _stream()))
+
+
+def spd_speculative_accept_static(target, draft, draft_tokens, u, temperature, flags, n_accepted_out, next_token_out,
+                                  accept_prob_out=None):
+    """spd_speculative_accept without a workspace argument (scratch memory inside the library); allocates nothing."""
+    n_seqs, g1, vocab = target.shape
+    gamma = g1 - 1
+    assert draft.shape == (n_seqs, gamma, vocab) and draft_tokens.shape == (n_seqs, gamma) and u.shape == (n_seqs, g1)
+    _check(_lib.spd_speculative_accept_static(_ptr(target, torch.float32), _ptr(draft, torch.float32),
+                                              _ptr(draft_tokens, torch.int32), _ptr(u, torch.float32), n_seqs, gamma, vocab,
+                                              float(temperature), int(flags), _ptr(n_accepted_out, torch.int32),
+                                              _ptr(next_token_out, torch.int32), _ptr(accept_prob_out, torch.float32), _stream()))

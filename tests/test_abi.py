@@ -114,6 +114,7 @@ def test_null_handles_are_refused_by_every_entry_point():
         "spd_draft_step": (null, null, i32(1), i32(1), f32(1.0), null, null, null, null),
         "spd_draft_step_strided": (null, null, i32(1), i32(1), i32(1), f32(1.0), null, i32(1), null, sz(16), null, i32(1), null),
         "spd_speculative_accept": (null, null, null, null, i32(1), i32(4), i32(16), f32(1.0), ctypes.c_uint32(0), null, null, null, null, sz(0), null),
+        "spd_speculative_accept_static": (null, null, null, null, i32(1), i32(4), i32(16), f32(1.0), ctypes.c_uint32(0), null, null, null, null),
         "spd_block_finish": (null, null, null, null, null, null, i32(1), i32(4), f32(1.0), null, null, null, null, i32(0), null, null, sz(0), null),
         "spd_trace_enable": (null, i32(1)),
         "spd_trace_read": (null, i32(8), null, null),
