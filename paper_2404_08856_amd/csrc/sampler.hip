@@ -51,8 +51,13 @@ __device__ unsigned long long block_exclusive_scan(unsigned long long v, unsigne
     return tmp[w] + incl - v;
 }
 
+// floor(r * 2^32) for r >= 0: the scale is exact (a power of two).  Below 1 -- every probability except an
+// exact 1 -- the result fits 32 bits and one truncating conversion instruction gives it; the general
+// float -> 64-bit conversion (a long instruction sequence) is only needed for r >= 1.
 __device__ __forceinline__ unsigned long long fixed_weight(float r) {
-    return (unsigned long long)(r * 4294967296.0f);          // exact scale, truncation
+    const float scaled = r * 4294967296.0f;
+    if (__builtin_expect(r >= 1.0f, 0)) return (unsigned long long)scaled;
+    return (unsigned long long)__float2uint_rz(scaled);
 }
 
 __device__ __forceinline__ unsigned long long threshold_of(float u, unsigned long long S) {
@@ -207,19 +212,17 @@ template <class WF>
 __device__ int sample_inverse_cdf_regs(WF wf, int V, float u, unsigned long long *tmp, int *result) {
     // tmp: kRowVec * 17 u64 of shared memory
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    // The 32 weights of a thread are recomputed where they are needed again instead of being
-    // kept (64 registers).  `salt` is zero, but only at run time, so that the two computations
-    // are not merged back into one long-lived value.
-    auto part_of = [&](int i, unsigned long long salt) {
+    // per slice: the sum of the thread's 4 weights, and its inclusive scan over the wave
+    unsigned long long part[kRowVec], incl[kRowVec];
+#pragma unroll
+    for (int i = 0; i < kRowVec; ++i) {
         const int x0 = 4 * (i * kSampThreads + (int)threadIdx.x);
         unsigned long long p = 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) p += (x0 + j < V) ? (wf(i, j, x0 + j) ^ salt) : 0ull;
-        return p;
-    };
-    unsigned long long incl[kRowVec];
-#pragma unroll
-    for (int i = 0; i < kRowVec; ++i) incl[i] = part_of(i, 0ull);
+        for (int j = 0; j < 4; ++j) p += (x0 + j < V) ? wf(i, j, x0 + j) : 0ull;
+        part[i] = p;
+        incl[i] = p;
+    }
 #pragma unroll
     for (int i = 0; i < kRowVec; ++i) {
 #pragma unroll
@@ -250,26 +253,22 @@ __device__ int sample_inverse_cdf_regs(WF wf, int V, float u, unsigned long long
         const unsigned long long excl = inc - v0 - v1;
         tmp[a0] = excl;
         tmp[a1] = excl + v0;
-        // slot 16 of slices 0 and 1 is free: the grand total, and a zero that nobody rewrites before every
-        // thread has passed the barrier at the end of this function (the run-time zero `salt` below)
-        if (lane == 63) { tmp[16] = inc; tmp[17 + 16] = 0ull; *result = -1; }
+        if (lane == 63) { tmp[16] = inc; *result = -1; }      // slot 16 of slice 0 is free: the grand total
     }
     __syncthreads();
     const unsigned long long S = tmp[16];
     if (S != 0) {
         const unsigned long long thr = threshold_of(u, S);
-        const unsigned long long salt = tmp[17 + 16];         // 0; read from memory that the matching thread below does not write
 #pragma unroll
         for (int i = 0; i < kRowVec; ++i) {
-            const unsigned long long part = part_of(i, salt);
-            const unsigned long long excl = tmp[i * 17 + w] + incl[i] - part;
-            if (excl <= thr && thr < excl + part) {           // exactly one (thread, slice)
+            const unsigned long long excl = tmp[i * 17 + w] + incl[i] - part[i];
+            if (excl <= thr && thr < excl + part[i]) {        // exactly one (thread, slice)
                 const int x0 = 4 * (i * kSampThreads + (int)threadIdx.x);
                 unsigned long long run = excl;
                 int found = -1;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    if (x0 + j < V) run += wf(i, j, x0 + j) ^ salt;
+                    if (x0 + j < V) run += wf(i, j, x0 + j);
                     if (found < 0 && run > thr) found = x0 + j;
                 }
                 *result = found;
@@ -374,15 +373,17 @@ __global__ __launch_bounds__(kSampThreads) void accept_decide_kernel(AcceptArgs 
         load_row(T.row, V, T.mode == 0 ? 0.f : -INFINITY, tv);
         if (k < G) {
             const RowProb D = d_row(k);
-            float4 dv[kRowVec];
-            load_row(D.row, V, D.mode == 0 ? 0.f : -INFINITY, dv);
+            const int n4 = V >> 2;
+            const float fill = D.mode == 0 ? 0.f : -INFINITY;
 #pragma unroll
-            for (int i = 0; i < kRowVec; ++i) {
-                const int x0 = 4 * (i * kSampThreads + (int)threadIdx.x);
-                tv[i].x = fmaxf(0.0f, __fsub_rn(T.of(tv[i].x, x0), D.of(dv[i].x, x0)));
-                tv[i].y = fmaxf(0.0f, __fsub_rn(T.of(tv[i].y, x0 + 1), D.of(dv[i].y, x0 + 1)));
-                tv[i].z = fmaxf(0.0f, __fsub_rn(T.of(tv[i].z, x0 + 2), D.of(dv[i].z, x0 + 2)));
-                tv[i].w = fmaxf(0.0f, __fsub_rn(T.of(tv[i].w, x0 + 3), D.of(dv[i].w, x0 + 3)));
+            for (int i = 0; i < kRowVec; ++i) {               // the draft row passes through 4 registers at a time
+                const int q = i * kSampThreads + (int)threadIdx.x;
+                const int x0 = 4 * q;
+                const float4 dq = q < n4 ? reinterpret_cast<const float4 *>(D.row)[q] : float4{fill, fill, fill, fill};
+                tv[i].x = fmaxf(0.0f, __fsub_rn(T.of(tv[i].x, x0), D.of(dq.x, x0)));
+                tv[i].y = fmaxf(0.0f, __fsub_rn(T.of(tv[i].y, x0 + 1), D.of(dq.y, x0 + 1)));
+                tv[i].z = fmaxf(0.0f, __fsub_rn(T.of(tv[i].z, x0 + 2), D.of(dq.z, x0 + 2)));
+                tv[i].w = fmaxf(0.0f, __fsub_rn(T.of(tv[i].w, x0 + 3), D.of(dq.w, x0 + 3)));
             }
         } else {
 #pragma unroll
