@@ -124,6 +124,10 @@ typedef struct {
     int32_t  gemm_waves[SPD_N_PROJECTIONS];          /* waves per workgroup: 4, 8 or 16; 0 = default */
     int32_t  gemm_grid_cap[SPD_N_PROJECTIONS];       /* upper bound of the grid; 0 = default         */
     int32_t  gemm_general_kernel[SPD_N_PROJECTIONS]; /* 1: never the register-resident variant       */
+    int32_t  batch_kernel;           /* calls of more than 10 rows: 0 = the library chooses per projection between the
+                                        tile-splitting batched kernel (one pass over the weights for up to 64 rows) and
+                                        the K-splitting kernels (passes of 40 rows); 1 = always the former, 2 = always
+                                        the latter */
     uint32_t wait_spin_limit;        /* polls before a wait between workgroups gives up and raises the flag that
                                         spd_device_status reports (0 = default, 2^22); a tiny value lets a test
                                         drive that error path from the host while every kernel still exits */
@@ -137,6 +141,14 @@ int32_t spd_model_set_tuning(spd_model *model, const spd_tuning *h_tuning);
  * max_seqs, SPD_ERR_INVALID_ARG on negative values. */
 int32_t spd_kv_set_len(spd_model *model, const int32_t *h_len_per_seq, int32_t n_seqs);
 int32_t spd_kv_get_len(const spd_model *model, int32_t *h_len_per_seq, int32_t n_seqs);
+
+/* Inspection (tests, baselines; not part of the method): the cached keys (after RoPE) and values of
+ * positions pos0 .. pos0+n-1 of one layer and sequence as float32 [n, n_heads, head_dim] each (the cache
+ * itself is bfloat16 in layouts of the library's own).  Positions need not be below the current KV
+ * length: whatever the cache holds there is returned.  Errors: SPD_ERR_INVALID_ARG, SPD_ERR_CAPACITY
+ * (positions outside max_positions). */
+int32_t spd_kv_export(spd_model *model, int32_t layer, int32_t seq, int32_t pos0, int32_t n,
+                      float *k_out, float *v_out, void *stream);
 
 /* Not hot: feeds n_rows input-embedding rows (float32 [n_rows, d_model],
  * e.g. [V_1..V_m ; E[X_1..X_n]] for the target, Section 2.2 Eq. 1) to sequence

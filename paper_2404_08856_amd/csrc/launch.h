@@ -40,7 +40,7 @@ size_t packed_matrix_bytes(int N, int K);
 
 // ---- skinny weight-streaming GEMM -------------------------------------------------
 enum Epilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
-struct GemmTuning { int waves; int grid_cap; int ring; int no_regb; };   // 0 = default for grid_cap / ring
+struct GemmTuning { int waves; int grid_cap; int ring; int no_regb; int no_batch; int force_batch; };   // 0 = default for grid_cap / ring
 struct GemmArgs {
     const void *W;        // packed weights [N, K]
     const void *X;        // packed activations (B operand blocks), K columns
@@ -60,7 +60,12 @@ struct GemmArgs {
     float *ssq_out;           // [64][N / 16] per-tile sums of squares of h_new
     void *Xout;           // SWIGLU: packed activations with K_out = N / 2 columns
     int K_out;
+    // more than 10 rows: scratch for the partial tiles of the K slices (gemm_batch_scratch_bytes) and the tile
+    // groups' arrival counters (1024 entries, zero between launches); NULL: the kernels that need neither
+    float *batch_partials;
+    unsigned *batch_arrive;
 };
+size_t gemm_batch_scratch_bytes(int N, int K);
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStream_t stream);
 
 // ---- row-wise kernels -------------------------------------------------------------
@@ -85,6 +90,9 @@ struct CommitArgs {
 };
 hipError_t launch_block_commit(const CommitArgs &a, hipStream_t stream);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t stream);
+// K and V of positions pos0 .. pos0 + n - 1 of one (layer, sequence) as float32 [n][H][dh] (k_cache / v_cache: that pair's slices)
+hipError_t launch_kv_export(const void *k_cache, const void *v_cache, int H, int dh, int max_positions, int pos0, int n,
+                            float *k_out, float *v_out, hipStream_t stream);
 
 // ---- attention ----------------------------------------------------------------------
 struct AttnArgs {

@@ -50,7 +50,7 @@ struct Layout {                    // byte offsets inside the three buffers
     size_t kv_layer_stride, kv_k_bytes, kv_v_bytes, kv_total;
     int v_stride;
     // workspace
-    size_t h, qkv, xn, xo, xf, rope, logits, ssq_a, ssq_b, d_lens, d_error, qa_count, qa_abort, ws_total;
+    size_t h, qkv, xn, xo, xf, rope, logits, ssq_a, ssq_b, d_lens, d_error, qa_count, qa_abort, part, arrive, ws_total;
 };
 
 int32_t check_shape(const spd_model_config &c) {
@@ -107,6 +107,12 @@ void make_layout(const spd_model_config &c, Layout &L) {
     L.qa_abort = take(4);
     L.ssq_a = take((size_t)(d / 16) * kMaxRows * 4);
     L.ssq_b = take((size_t)(d / 16) * kMaxRows * 4);
+    size_t pb = 0;
+    for (size_t b : {gemm_batch_scratch_bytes(3 * HD, d), gemm_batch_scratch_bytes(d, HD), gemm_batch_scratch_bytes(2 * F, d),
+                     gemm_batch_scratch_bytes(d, F), gemm_batch_scratch_bytes(V, d)})
+        pb = b > pb ? b : pb;
+    L.part = take(pb);
+    L.arrive = take(1024 * 4);
     L.ws_total = off;
 }
 
@@ -119,6 +125,8 @@ GemmTuning default_tuning(int N, int K) {
     t.grid_cap = 0;
     t.ring = 8;
     t.no_regb = 0;
+    t.no_batch = 0;
+    t.force_batch = 0;
     if (KS == 128) t.waves = tiles >= 1024 ? 16 : 8;    // gate|up, LM head: 16 waves x 8 steps measured 1-2 % faster
     else if (KS == 64) t.waves = 8;
     else if (KS == 32) t.waves = 4;
@@ -312,6 +320,7 @@ int32_t spd_model_create(const spd_model_config *cfg, const spd_weights *w, void
 
 int32_t spd_model_set_tuning(spd_model *m, const spd_tuning *t) {
     if (!m || !t) return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_model_set_tuning");
+    if (t->batch_kernel < 0 || t->batch_kernel > 2) return fail(SPD_ERR_INVALID_ARG, "batch_kernel must be 0, 1 or 2");
     if (t->separate_qkv_attention != 0 && t->separate_qkv_attention != 1) return fail(SPD_ERR_INVALID_ARG, "separate_qkv_attention must be 0 or 1");
     if (t->attention_slices != 0 && t->attention_slices != 1 && t->attention_slices != 2 && t->attention_slices != 4 &&
         t->attention_slices != 8)
@@ -330,6 +339,8 @@ int32_t spd_model_set_tuning(spd_model *m, const spd_tuning *t) {
         if (t->gemm_waves[i]) gt[i]->waves = t->gemm_waves[i];
         gt[i]->grid_cap = t->gemm_grid_cap[i];
         gt[i]->no_regb = t->gemm_general_kernel[i] ? 1 : 0;
+        gt[i]->no_batch = t->batch_kernel == 2 ? 1 : 0;
+        gt[i]->force_batch = t->batch_kernel == 1 ? 1 : 0;
     }
     m->fuse_qa = t->separate_qkv_attention ? false : m->fuse_qa_ok;
     m->fuse_qa2 = t->separate_qkv_attention ? false : m->fuse_qa2_ok;
@@ -386,6 +397,19 @@ int32_t spd_device_status(spd_model *m, void *stream) {
     HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
     if (flags[1]) return fail(SPD_ERR_HIP, "a wait between workgroups hit its spin limit: results since then are invalid");
     if (flags[0]) return fail(SPD_ERR_CAPACITY, "a forward ran with a device KV length that left no room for its rows");
+    return SPD_OK;
+}
+
+int32_t spd_kv_export(spd_model *m, int32_t layer, int32_t seq, int32_t pos0, int32_t n, float *k_out, float *v_out, void *stream) {
+    if (!m || !k_out || !v_out) return fail(SPD_ERR_INVALID_ARG, "NULL argument to spd_kv_export");
+    const spd_model_config &c = m->cfg;
+    if (layer < 0 || layer >= c.n_layers || seq < 0 || seq >= c.max_seqs) return fail(SPD_ERR_INVALID_ARG, "layer / sequence index out of range");
+    if (n < 1 || pos0 < 0 || pos0 + n > c.max_positions) return fail(SPD_ERR_CAPACITY, "positions %d..%d outside the cache (%d)", pos0, pos0 + n - 1, c.max_positions);
+    const Layout &L = m->L;
+    const char *kv_l = m->kv + (size_t)layer * L.kv_layer_stride;
+    const char *k = kv_l + (size_t)seq * c.n_heads * c.max_positions * c.head_dim * 2;
+    const char *v = kv_l + align_up(L.kv_k_bytes, 256) + (size_t)seq * c.n_heads * c.head_dim * L.v_stride * 2;
+    HIP_TRY(launch_kv_export(k, v, c.n_heads, c.head_dim, c.max_positions, pos0, n, k_out, v_out, (hipStream_t)stream));
     return SPD_OK;
 }
 
@@ -454,6 +478,7 @@ int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const flo
         at.k_cache = kv_l + (size_t)seq0 * c.n_heads * c.max_positions * c.head_dim * 2;
         at.v_cache = kv_l + align_up(L.kv_k_bytes, 256) + (size_t)seq0 * c.n_heads * c.head_dim * L.v_stride * 2;
         GemmArgs g{};
+        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive);
         if (fused) {
             QkvAttnArgs qa{};
             qa.W = m->packed + L.wqkv[l]; qa.X = xn; qa.K = d; qa.rows = rows;
@@ -473,20 +498,24 @@ int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const flo
             }
         }
         g = GemmArgs{};
+        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive);
         g.W = m->packed + L.wo[l]; g.X = xo; g.N = d; g.K = HD; g.rows = rows; g.Y = h; g.ldy = d;
         g.gain_next = gain_of(L.mlp_norm[l]); g.Xnext = xn; g.ssq_out = ssq_a;
         PROF_GEMM(PK_O, launch_gemm(g, EPI_RESIDUAL, m->t_o, st));
         g = GemmArgs{};
+        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive);
         g.W = m->packed + L.wgu[l]; g.X = xn; g.N = 2 * F; g.K = d; g.rows = rows; g.Xout = xf; g.K_out = F;
         g.ssq_in = ssq_a; g.ssq_in_parts = d_tiles; g.eps = c.rms_eps;
         PROF_GEMM(PK_GATE_UP, launch_gemm(g, EPI_SWIGLU, m->t_gu, st));
         g = GemmArgs{};
+        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive);
         g.W = m->packed + L.wdown[l]; g.X = xf; g.N = d; g.K = F; g.rows = rows; g.Y = h; g.ldy = d;
         g.gain_next = gain_of(l + 1 < c.n_layers ? L.attn_norm[l + 1] : L.final_norm); g.Xnext = xn; g.ssq_out = ssq_b;
         PROF_GEMM(PK_DOWN, launch_gemm(g, EPI_RESIDUAL, m->t_down, st));
     }
     if (logits_out) {
         GemmArgs g{};
+        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive);
         g.W = m->packed + L.lm_head; g.X = xn; g.N = V; g.K = d; g.rows = rows; g.Y = logits_out; g.ldy = V;
         g.ssq_in = ssq_b; g.ssq_in_parts = d_tiles; g.eps = c.rms_eps;
         PROF_GEMM(PK_LM_HEAD, launch_gemm(g, EPI_STORE, m->t_lm, st));

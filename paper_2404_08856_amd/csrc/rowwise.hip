@@ -106,6 +106,31 @@ hipError_t launch_block_commit(const CommitArgs &a, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// ---- KV cache read-out (inspection: tests, the benchmark's CPU baseline) -------------------
+// K[pos][head][d] and V[pos][head][d] of one (layer, sequence) as float32, from the cache's own layouts:
+// K bf16 [head][pos][dh], V bf16 [head][v_stride / 32][dh][32].
+__global__ void kv_export_kernel(const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Vt, int H, int dh, int max_positions,
+                                 int pos0, int n, float *__restrict__ k_out, float *__restrict__ v_out) {
+    const size_t total = (size_t)n * H * dh;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int d = (int)(i % dh), h = (int)((i / dh) % H), p = (int)(i / ((size_t)dh * H));
+        const int pos = pos0 + p;
+        k_out[i] = bf16_bits_to_f32(Kc[((size_t)h * max_positions + pos) * dh + d]);
+        v_out[i] = bf16_bits_to_f32(Vt[(((size_t)h * ((max_positions + 31) / 32) + (pos >> 5)) * dh + d) * 32 + (pos & 31)]);
+    }
+}
+
+hipError_t launch_kv_export(const void *k_cache, const void *v_cache, int H, int dh, int max_positions, int pos0, int n,
+                            float *k_out, float *v_out, hipStream_t stream) {
+    if (n < 1 || pos0 < 0 || pos0 + n > max_positions) return hipErrorInvalidValue;
+    const size_t total = (size_t)n * H * dh;
+    unsigned grid = (unsigned)((total + 255) / 256);
+    if (grid > 4096) grid = 4096;
+    hipLaunchKernelGGL(kv_export_kernel, dim3(grid), dim3(256), 0, stream, (const uint16_t *)k_cache, (const uint16_t *)v_cache, H, dh,
+                       max_positions, pos0, n, k_out, v_out);
+    return hipGetLastError();
+}
+
 __global__ void fill_zero_kernel(uint4 *p, size_t n16) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t stride = (size_t)gridDim.x * blockDim.x;

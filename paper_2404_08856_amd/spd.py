@@ -26,7 +26,7 @@ EXPORTS = ["spd_last_error", "spd_model_bytes", "spd_model_create", "spd_model_d
            "spd_kv_get_len", "spd_prefill", "spd_prefill_tokens", "spd_verify_forward", "spd_draft_step",
            "spd_accept_workspace_bytes", "spd_speculative_accept", "spd_trace_enable", "spd_trace_read",
            "spd_model_set_tuning", "spd_kv_lens_to_device", "spd_kv_lens_from_device", "spd_draft_step_strided",
-           "spd_block_finish", "spd_device_status", "spd_speculative_accept_static"]
+           "spd_block_finish", "spd_device_status", "spd_speculative_accept_static", "spd_kv_export"]
 TRACE_KINDS = ["qkv", "o", "gate_up", "down", "lm_head", "attention", "embed"]
 PROJECTIONS = ["qkv", "o", "gate_up", "down", "lm_head"]
 
@@ -48,7 +48,8 @@ class spd_model_config(ctypes.Structure):
 class spd_tuning(ctypes.Structure):
     _fields_ = [("separate_qkv_attention", ctypes.c_int32), ("attention_slices", ctypes.c_int32),
                 ("gemm_waves", ctypes.c_int32 * 5), ("gemm_grid_cap", ctypes.c_int32 * 5),
-                ("gemm_general_kernel", ctypes.c_int32 * 5), ("wait_spin_limit", ctypes.c_uint32)]
+                ("gemm_general_kernel", ctypes.c_int32 * 5), ("batch_kernel", ctypes.c_int32),
+                ("wait_spin_limit", ctypes.c_uint32)]
 
 
 _PP = ctypes.POINTER(ctypes.c_void_p)
@@ -71,6 +72,7 @@ _lib.spd_model_destroy.argtypes = [_vp]
 _lib.spd_model_set_tuning.argtypes = [_vp, ctypes.POINTER(spd_tuning)]
 _lib.spd_kv_set_len.argtypes = [_vp, ctypes.POINTER(_i32), _i32]
 _lib.spd_kv_get_len.argtypes = [_vp, ctypes.POINTER(_i32), _i32]
+_lib.spd_kv_export.argtypes = [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
 _lib.spd_prefill.argtypes = [_vp, _i32, _vp, _i32, _vp, _vp]
 _lib.spd_prefill_tokens.argtypes = [_vp, _i32, _vp, _i32, _vp, _vp]
 _lib.spd_verify_forward.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp]
@@ -171,10 +173,11 @@ class Model:
 
     # --- thin wrappers, same names as the C entry points ---------------------------------
     def spd_model_set_tuning(self, separate_qkv_attention=0, attention_slices=0, gemm_waves=None, gemm_grid_cap=None,
-                             gemm_general_kernel=None, wait_spin_limit=0):
+                             gemm_general_kernel=None, batch_kernel=0, wait_spin_limit=0):
         """Kernel-selection knobs for tests and sweeps; the per-projection dicts are keyed by PROJECTIONS."""
         t = spd_tuning()
         t.separate_qkv_attention, t.attention_slices, t.wait_spin_limit = int(separate_qkv_attention), int(attention_slices), int(wait_spin_limit)
+        t.batch_kernel = int(batch_kernel)
         for field, given in (("gemm_waves", gemm_waves), ("gemm_grid_cap", gemm_grid_cap), ("gemm_general_kernel", gemm_general_kernel)):
             for name, value in (given or {}).items():
                 getattr(t, field)[PROJECTIONS.index(name)] = int(value)
@@ -188,6 +191,11 @@ class Model:
         a = (ctypes.c_int32 * n_seqs)()
         _check(_lib.spd_kv_get_len(self.handle, a, n_seqs))
         return list(a)
+
+    def spd_kv_export(self, layer, seq, pos0, k_out, v_out):
+        n = k_out.shape[0]
+        assert k_out.shape == v_out.shape == (n, self.cfg.n_heads, self.cfg.head_dim)
+        _check(_lib.spd_kv_export(self.handle, layer, seq, pos0, n, _ptr(k_out, torch.float32), _ptr(v_out, torch.float32), _stream()))
 
     def spd_prefill(self, seq, embeds, last_logits=None):
         _check(_lib.spd_prefill(self.handle, seq, _ptr(embeds, torch.float32), embeds.shape[0],

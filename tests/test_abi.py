@@ -108,6 +108,7 @@ def test_null_handles_are_refused_by_every_entry_point():
         "spd_kv_lens_to_device": (null, null),
         "spd_kv_lens_from_device": (null, null),
         "spd_device_status": (null, null),
+        "spd_kv_export": (null, i32(0), i32(0), i32(0), i32(1), null, null, null),
         "spd_prefill": (null, i32(0), null, i32(1), null, null),
         "spd_prefill_tokens": (null, i32(0), null, i32(1), null, null),
         "spd_verify_forward": (null, null, i32(1), i32(5), null, null),

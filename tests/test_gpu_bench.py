@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 @pytest.mark.timeout(600)
 def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "5", "--warmup", "1", "--no-side-configs",
-                        "--cpu-layers", "1"], capture_output=True, text=True, timeout=580)
+                        "--cpu-reps", "1"], capture_output=True, text=True, timeout=580)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [l for l in r.stdout.splitlines() if l.strip()]
     assert len(lines) == 1

@@ -478,13 +478,17 @@ def test_image_aware_draft_takes_embedding_rows():
     model.close()
 
 
-@pytest.mark.parametrize("n_seqs,M", [(2, 4), (3, 7), (8, 8), (1, 6), (1, 8), (2, 5)])
-def test_batched_verify_wide_model(n_seqs, M):
-    """Several row groups on a model whose matrices have 256 and more tiles (d_model 4096): the
-    multi-group projection kernel with one and with three tiles in flight, all three epilogues."""
-    print(f"case batched wide n_seqs={n_seqs} M={M}", flush=True)
+@pytest.mark.parametrize("batch_kernel", [0, 1, 2])
+@pytest.mark.parametrize("n_seqs,M", [(2, 4), (3, 7), (8, 8), (1, 6), (1, 8), (2, 5), (5, 4), (8, 5), (7, 8)])
+def test_batched_verify_wide_model(n_seqs, M, batch_kernel):
+    """Several row groups on a model whose matrices have 256 and more tiles (d_model 4096), all three
+    epilogues: the tile-splitting batched kernel (11..64 rows: 4, 8 or 13 row groups, K split across
+    workgroups, last arriver reduces) and, with it switched off, the K-splitting multi-group kernel with
+    one and with three tiles in flight."""
+    print(f"case batched wide n_seqs={n_seqs} M={M} batch_kernel={batch_kernel}", flush=True)
     shape = synth.ModelShape(1, 4096, 2, 128, 3072, 1024)       # gate|up: 384 tiles, O / down: 256 tiles
     model, wn = build_pair(shape, 57, n_seqs, 48)
+    model.spd_model_set_tuning(batch_kernel=batch_kernel)      # 0: the library's choice, 1: always tile-splitting, 2: never
     cfg = oracle_cfg(shape)
     caches = []
     for s in range(n_seqs):
@@ -580,4 +584,40 @@ def test_long_context_batch_with_unsliced_heads():
         got = out.cpu().numpy()
         for s in range(3):
             check_logits(got[s], dec.forward_tokens(cfg, wn, caches[s], vt[s]), f"slices {slices} seq {s}")
+    model.close()
+
+
+@pytest.mark.parametrize("shape_name,m_img,n_text", [("tiny_target", 7, 30), ("tiny_draft", 0, 45)])
+def test_kv_cache_contents_match_the_oracle(shape_name, m_img, n_text):
+    """RoPE + KV append seen directly: after a prefill and a 5-token step the cached keys (after RoPE) and
+    values, read back through spd_kv_export, are the oracle's cache entries -- bfloat16 values on both sides,
+    so they are equal except where the float32 and float64 paths fall on different sides of a rounding
+    boundary (one bfloat16 step apart, and rare; or, for values near zero, the float32 rounding error itself)."""
+    shape = synth.SHAPES[shape_name]
+    model, wn = build_pair(shape, 91, 1, 64)
+    cfg = oracle_cfg(shape)
+    toks = synth.text_tokens(n_text, shape.vocab, 91)
+    x = dec.embed_tokens(wn, toks)
+    if m_img:
+        x = np.concatenate([synth.image_rows(m_img, shape.d_model, 91).astype(np.float64), x])
+    cache = dec.KVCache(cfg, 64)
+    dec.forward_rows(cfg, wn, cache, x)
+    model.spd_prefill(0, torch.from_numpy(x.astype(np.float32)).cuda())
+    vt = synth.text_tokens(5, shape.vocab, 92)
+    dec.forward_tokens(cfg, wn, cache, vt)
+    out = torch.empty((1, 5, shape.vocab), dtype=torch.float32, device="cuda")
+    model.spd_verify_forward(torch.from_numpy(vt).cuda()[None].contiguous(), out)
+    P = cache.length
+    assert model.spd_kv_get_len(1) == [P]
+    for l in range(shape.n_layers):
+        k = torch.empty((P, shape.n_heads, shape.head_dim), dtype=torch.float32, device="cuda")
+        v = torch.empty_like(k)
+        model.spd_kv_export(l, 0, 0, k, v)
+        for name, got, want in (("K", k.cpu().numpy().astype(np.float64), cache.k[l, :P]), ("V", v.cpu().numpy().astype(np.float64), cache.v[l, :P])):
+            diff = np.abs(got - want)
+            # at most one bfloat16 step at the value's magnitude; values near zero (cancellation in the rotation)
+            # carry the absolute float32 error of the sums that produced them instead
+            step = np.maximum(np.abs(want) * 2.0 ** -7, 1e-5 * np.sqrt(np.mean(want * want)))
+            assert np.all(diff <= step), (name, l, float(diff.max()))
+            assert np.mean(diff > 0) < 0.02, (name, l, float(np.mean(diff > 0)))
     model.close()
