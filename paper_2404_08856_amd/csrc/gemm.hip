@@ -394,21 +394,21 @@ static hipError_t launch_multi(const GemmKernelArgs &k, int epilogue, int grid, 
 // terms = 1 MiB), so a kernel whose waves split K re-reads it from L2 for every few tiles and is bound by
 // that traffic, not by HBM.  Here the waves of a workgroup split TILES instead: all 8 waves walk the same
 // K range, each with its own TT tiles, so an activation block is fetched once per workgroup (into LDS, CH
-// K-steps at a time, double buffered) and used by 8 * TT tiles.  No cross-wave reduction is needed.  To keep
+// K-steps at a time, several chunks ahead) and used by 8 * TT tiles.  No cross-wave reduction is needed.  To keep
 // enough workgroups for the chip the K range is split ACROSS workgroups (J slices): every workgroup writes
 // its partial tiles to a scratch buffer and counts itself in on its tile group's arrival counter; the one
 // that arrives last (its ticket says so -- nobody ever waits) adds the J partials in slice order and runs
 // the epilogue, then clears the counter for the next launch.  Fixed order => bit-reproducible.  The partials
 // cross workgroups (and XCDs, each with its own L2) inside one launch: device-scope stores, acknowledged
 // before the arrival is counted, and device-scope loads.
-constexpr int kBatchWaves = 8, kBatchMaxJ = 8;
+constexpr int kBatchWaves = 8, kBatchMaxJ = 4;
 constexpr int kBatchCH = 4;      // K-steps per activation chunk: two LDS buffers of NG * CH KiB each
 // chunks the weight ring runs ahead (registers: TT * RDC * CH * 4 for the ring next to TT * NG * 4 accumulators)
 constexpr int batch_ring_chunks(int NG, int TT) { return (TT * NG * 4 + TT * 2 * kBatchCH * 4 <= 144) ? 2 : 1; }
 
 struct BatchPlan { int TT, J, n_tgroups; };
 // TT tiles per wave (2 where the matrix has the tiles for it; accumulators = TT * NG * 4 VGPRs, weight ring
-// = TT * CH blocks in flight per wave); J K-slices (at most 8: the last arriver reads J partials per
+// = TT * CH blocks in flight per wave); J K-slices (at most 4: the last arriver reads J partials per
 // output) so that there is about one workgroup per CU.
 static BatchPlan batch_plan(int n_tiles, int KS, int NG) {
     BatchPlan p;
@@ -435,73 +435,34 @@ size_t gemm_batch_scratch_bytes(int N, int K) {
     return worst;
 }
 
-struct BatchArgs { float *partials; unsigned *arrive; int J; };
+struct BatchArgs { float *partials; unsigned *arrive; int J; const uint4 *zero_block; };
+
+// Two loader waves next to the 8 multiplying waves bring the activation chunks into LDS with LDS-direct loads (no
+// registers, asynchronous), NBUF - 1 chunks ahead of the products; a wave can have 63 loads outstanding, which
+// bounds (NBUF - 1) * blocks per loader wave and chunk.
+constexpr int kBatchLoaders = 2;
+constexpr int batch_buffers(int NG) { return NG <= 8 ? 4 : 3; }
 
 template <int NG, int TT, int EPI>
-__global__ __launch_bounds__(kBatchWaves * 64) void gemm_batch_kernel(GemmKernelArgs a, BatchArgs b) {
-    constexpr int WAVES = kBatchWaves, CH = kBatchCH, RDC = batch_ring_chunks(NG, TT);
+__global__ __launch_bounds__((kBatchWaves + kBatchLoaders) * 64) void gemm_batch_kernel(GemmKernelArgs a, BatchArgs b) {
+    constexpr int WAVES = kBatchWaves, LW = kBatchLoaders, CH = kBatchCH, RDC = batch_ring_chunks(NG, TT), NBUF = batch_buffers(NG);
     constexpr int TPG = WAVES * TT;                        // tiles per workgroup
+    constexpr int PB = (NG * CH + LW - 1) / LW;            // activation blocks per loader wave and chunk
+    static_assert((NBUF - 1) * PB <= 63, "outstanding loads of a loader wave");
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int KS = a.KS, J = b.J;
     const int j = blockIdx.x % J, tg = blockIdx.x / J;     // K slice fastest: the slices of a tile group start together
     // K slices are whole units of RDC chunks of CH K-steps; the last unit of the matrix may be ragged (its missing
-    // K-steps get zero activations), so the loop below has no conditional parts and every wait counts exactly
+    // K-steps get zero activations), so the loops below have no conditional parts and every wait counts exactly
     const int n_units = (KS + RDC * CH - 1) / (RDC * CH);
     const int c_begin = RDC * (int)(((long)n_units * j) / J), c_end = RDC * (int)(((long)n_units * (j + 1)) / J);
     const int g0 = a.row0 / kGroupRows;
     const int ngv = (a.rows + kGroupRows - 1) / kGroupRows;    // row groups that hold rows of this pass (<= NG)
 
-    __shared__ uint4 Xs[2][NG][CH][64];
+    __shared__ uint4 Xs[NBUF][NG][CH][64];
     __shared__ float inv_s[kMaxRows];
     __shared__ int is_last;
-
-    int tile[TT];
-#pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-        const int t = (tg * WAVES + w) * TT + tt;
-        tile[tt] = t < a.n_tiles ? t : a.n_tiles - 1;         // beyond the matrix: a valid tile, result dropped
-    }
-    // activation chunk (NG groups x CH K-steps = NG * CH blocks of 1 KiB) -> registers -> LDS; wave w moves
-    // blocks w, w + 8, ...
-    constexpr int XB = (NG * CH + WAVES - 1) / WAVES;        // blocks per wave and chunk
-    struct Chunk { uint4 v[XB]; };
-    auto load_chunk = [&](int c) __attribute__((always_inline)) {
-        Chunk x;
-        const int cc = c < c_end ? c : c_begin;               // past the slice: a harmless re-read
-#pragma unroll
-        for (int r = 0; r < XB; ++r) {
-            const int blk = w + r * WAVES;                    // wave-uniform
-            const int bb = blk < NG * CH ? blk : 0;
-            const int k = bb % CH, g = bb / CH;
-            const int s = cc * CH + k;
-            const uint4 v = a.X[((size_t)(g0 + (g < ngv ? g : 0)) * KS + (s < KS ? s : KS - 1)) * 64 + lane];
-            x.v[r] = s < KS ? v : uint4{0u, 0u, 0u, 0u};      // K-steps beyond the matrix contribute nothing
-        }
-        return x;
-    };
-    auto store_chunk = [&](int buf, const Chunk &x) __attribute__((always_inline)) {
-#pragma unroll
-        for (int r = 0; r < XB; ++r) {
-            const int blk = w + r * WAVES;
-            if (blk < NG * CH) Xs[buf][blk / CH][blk % CH][lane] = x.v[r];
-        }
-    };
-    // weight ring of this wave: RDC chunks ahead for each of its TT tiles; chunk c uses slots (c % RDC) * CH + k
-    uint4 ring[TT][RDC * CH];
-    auto refill = [&](int tt, int slot, int k, int c) __attribute__((always_inline)) {   // block (tile, K-step k of chunk c)
-        int s = (c < c_end ? c : c_begin) * CH + k;           // past the slice: a harmless re-read
-        s = s < KS ? s : KS - 1;
-        ring[tt][slot] = load_stream(a.W + ((size_t)tile[tt] * KS + s) * 64 + lane);
-    };
-#pragma unroll
-    for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-        for (int h = 0; h < RDC; ++h)
-#pragma unroll
-            for (int k = 0; k < CH; ++k) refill(tt, h * CH + k, k, c_begin + h);
-    store_chunk(0, load_chunk(c_begin));
-    __syncthreads();
 
     f32x4_t acc[TT][NG];
 #pragma unroll
@@ -509,49 +470,103 @@ __global__ __launch_bounds__(kBatchWaves * 64) void gemm_batch_kernel(GemmKernel
 #pragma unroll
         for (int g = 0; g < NG; ++g) acc[tt][g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    int buf = 0;
-    for (int c0 = c_begin; c0 < c_end; c0 += RDC) {
+    if (w >= WAVES) {
+        // ---- loader waves: chunk c + NBUF - 1 is requested while chunk c is multiplied; their loads wait in
+        // their own queues, so the multiplying waves' weight rings are never held up by them ----
+        auto issue_chunk = [&](int c) __attribute__((always_inline)) {
+            const int cc = c < c_end ? c : c_begin;           // past the slice: a harmless re-read
+            const int bufi = (c - c_begin) % NBUF;
 #pragma unroll
-        for (int h = 0; h < RDC; ++h, buf ^= 1) {
-            const int c = c0 + h;
-            const Chunk nxt = load_chunk(c + 1);              // in flight while this chunk is multiplied
-            __builtin_amdgcn_sched_barrier(0);                // issue order: next activations, then per K-step products + refills
-#pragma unroll
-            for (int k = 0; k < CH; ++k) {
-#pragma unroll
-                for (int g = 0; g < NG; ++g) {
-                    const uint4 bq = Xs[buf][g][k][lane];
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) acc[tt][g] = mfma_bf16(ring[tt][h * CH + k], bq, acc[tt][g]);
-                }
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) refill(tt, h * CH + k, k, c + RDC);
-                __builtin_amdgcn_sched_barrier(0);
+            for (int r = 0; r < PB; ++r) {
+                const int blk = (w - WAVES) + r * LW;         // wave-uniform
+                const int bb = blk < NG * CH ? blk : 0;       // (an odd block count: the last one twice)
+                const int k = bb % CH, g = bb / CH;
+                const int s = cc * CH + k;
+                // K-steps beyond the matrix read a block of zeros: they contribute nothing
+                const uint4 *src = (s < KS ? a.X + ((size_t)(g0 + (g < ngv ? g : 0)) * KS + s) * 64 : b.zero_block) + lane;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                                 (__attribute__((address_space(3))) void *)&Xs[bufi][g][k][0], 16, 0, 0);
             }
-            store_chunk(buf ^ 1, nxt);
-            __syncthreads();
+        };
+#pragma unroll
+        for (int i = 0; i < NBUF - 1; ++i) issue_chunk(c_begin + i);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NBUF - 2) * PB) : "memory");   // chunk c_begin has landed (loads complete in order)
+        __builtin_amdgcn_s_barrier();
+        for (int c = c_begin; c < c_end; ++c) {
+            issue_chunk(c + NBUF - 1);                        // into the buffer the products left one iteration ago
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NBUF - 2) * PB) : "memory");   // chunk c + 1 has landed
+            __builtin_amdgcn_s_barrier();
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+        // ---- multiplying waves: TT tiles each, weight ring RDC chunks ahead; chunk c uses slots (c % RDC) * CH + k ----
+        int tile[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            const int t = (tg * WAVES + w) * TT + tt;
+            tile[tt] = t < a.n_tiles ? t : a.n_tiles - 1;     // beyond the matrix: a valid tile, result dropped
+        }
+        uint4 ring[TT][RDC * CH];
+        auto refill = [&](int tt, int slot, int k, int c) __attribute__((always_inline)) {   // block (tile, K-step k of chunk c)
+            int s = (c < c_end ? c : c_begin) * CH + k;       // past the slice: a harmless re-read
+            s = s < KS ? s : KS - 1;
+            ring[tt][slot] = load_stream(a.W + ((size_t)tile[tt] * KS + s) * 64 + lane);
+        };
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int h = 0; h < RDC; ++h)
+#pragma unroll
+                for (int k = 0; k < CH; ++k) refill(tt, h * CH + k, k, c_begin + h);
+        __syncthreads();
+        int bufi = 0;
+        for (int c0 = c_begin; c0 < c_end; c0 += RDC) {
+#pragma unroll
+            for (int h = 0; h < RDC; ++h) {
+#pragma unroll
+                for (int k = 0; k < CH; ++k) {
+#pragma unroll
+                    for (int g = 0; g < NG; ++g) {
+                        const uint4 bq = Xs[bufi][g][k][lane];
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt) acc[tt][g] = mfma_bf16(ring[tt][h * CH + k], bq, acc[tt][g]);
+                    }
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) refill(tt, h * CH + k, k, c0 + h + RDC);
+                    __builtin_amdgcn_sched_barrier(0);        // keep "multiply, refill the freed slots" in program order
+                }
+                bufi = bufi + 1 == NBUF ? 0 : bufi + 1;
+                __syncthreads();
+            }
         }
     }
 
     // ---- partial tiles of this K slice -> scratch: P[slice][tile][group][row slot c < 5][column n < 16] ----
+    // Through LDS (the activation buffers are free now), so that the stores to memory are whole, contiguous lines:
+    // device-scope stores are written through, and pieces of lines cost the memory a read-modify-write each.
+    __syncthreads();                                      // the loaders' last (surplus) chunks have landed: the buffers are free
+    float *stage = reinterpret_cast<float *>(&Xs[0][0][0][0]);
+    static_assert(sizeof(Xs) >= (size_t)TPG * NG * 80 * sizeof(float), "staging area");
     const int r = lane & 15, grp = lane >> 4;
+    if (w < WAVES) {
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-        const int tl = w * TT + tt;                           // tile within the group
+        for (int tt = 0; tt < TT; ++tt) {
+            const int tl = w * TT + tt;                       // tile within the group
 #pragma unroll
-        for (int g = 0; g < NG; ++g) {
-            float4 v4;
-            v4.x = sum_terms(acc[tt][g][0]); v4.y = sum_terms(acc[tt][g][1]);
-            v4.z = sum_terms(acc[tt][g][2]); v4.w = sum_terms(acc[tt][g][3]);
-            if (r < kGroupRows) {                             // device-scope (write-through) stores, 8 bytes each
-                unsigned long long *dst = reinterpret_cast<unsigned long long *>(
-                    b.partials + ((((size_t)(tg * J + j) * TPG + tl) * NG + g) * kGroupRows + r) * 16 + 4 * grp);
-                const unsigned long long lo = (unsigned long long)__float_as_uint(v4.x) | ((unsigned long long)__float_as_uint(v4.y) << 32);
-                const unsigned long long hi = (unsigned long long)__float_as_uint(v4.z) | ((unsigned long long)__float_as_uint(v4.w) << 32);
-                __hip_atomic_store(dst, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(dst + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int g = 0; g < NG; ++g) {
+                float4 v4;
+                v4.x = sum_terms(acc[tt][g][0]); v4.y = sum_terms(acc[tt][g][1]);
+                v4.z = sum_terms(acc[tt][g][2]); v4.w = sum_terms(acc[tt][g][3]);
+                if (r < kGroupRows) *reinterpret_cast<float4 *>(stage + (((size_t)tl * NG + g) * kGroupRows + r) * 16 + 4 * grp) = v4;
             }
         }
+    }
+    __syncthreads();
+    {
+        const unsigned long long *src = reinterpret_cast<const unsigned long long *>(stage);
+        unsigned long long *dst = reinterpret_cast<unsigned long long *>(b.partials + (size_t)(tg * J + j) * TPG * NG * 80);
+        for (int i = threadIdx.x; i < TPG * NG * 40; i += (WAVES + LW) * 64)
+            __hip_atomic_store(dst + i, src[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     // once the partials are acknowledged, count this workgroup in; the last one to arrive finishes the tiles
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -562,98 +577,125 @@ __global__ __launch_bounds__(kBatchWaves * 64) void gemm_batch_kernel(GemmKernel
     }
     __syncthreads();
     if (!is_last) return;
-    // the other slices' partials were written through to memory by workgroups on other XCDs: drop whatever this
-    // XCD's caches still hold of the scratch buffer (from an earlier launch), then read with ordinary loads
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     if (threadIdx.x == 0) __hip_atomic_store(b.arrive + tg, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
 
-    if (a.ssq_in) {                                           // 1 / rms of every input row of this pass (fixed order)
-        for (int row = a.row0 + w; row < a.row0 + a.rows; row += WAVES) {
-            float sum = 0.f;
-            for (int p = lane; p < a.ssq_in_parts; p += 64) sum += a.ssq_in[(size_t)row * (KS * 2) + p];
+    // Four columns (tile, group, row slot c, columns 4 q .. 4 q + 3) per thread and item; q fastest: the 16
+    // columns of a (row, tile) sit in 4 neighbouring lanes.  The other slices' partials were written through to
+    // memory by workgroups on other XCDs: device-scope loads of 8 bytes.  All loads of up to four items are issued
+    // before anything is used, and before the rows' 1 / rms is worked out, so the tail costs about two round trips.
+    constexpr int NT = (WAVES + LW) * 64;
+    constexpr int ITEMS = TPG * NG * kGroupRows * 4;
+    constexpr int IPB = 4;                                    // items in flight per thread
+    for (int e0 = threadIdx.x; e0 - (int)threadIdx.x < ITEMS; e0 += NT * IPB) {
+        unsigned long long lo[IPB][kBatchMaxJ], hi[IPB][kBatchMaxJ];
+        float4 h4[IPB];
+        bool ok[IPB];
 #pragma unroll
-            for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-            if (lane == 0) inv_s[row] = 1.0f / sqrtf(sum * a.inv_d + a.eps);
-        }
-    } else if (threadIdx.x < kMaxRows) {
-        inv_s[threadIdx.x] = 1.0f;
-    }
-    __syncthreads();
-
-    // four columns (tile, group, row slot c, columns 4 q .. 4 q + 3) per thread and round; q fastest: the 16
-    // columns of a (row, tile) sit in 4 neighbouring lanes
-    for (int e = threadIdx.x; e < TPG * NG * kGroupRows * 4; e += WAVES * 64) {
-        const int q = e & 3, c = (e >> 2) % kGroupRows, g = (e / (4 * kGroupRows)) % NG, tl = e / (4 * kGroupRows * NG);
-        const int t = tg * TPG + tl;
-        const int erow = a.row0 + g * kGroupRows + c;
-        const bool ok = erow < a.row0 + a.rows && t < a.n_tiles;
-        float4 sum = float4{0.f, 0.f, 0.f, 0.f};
-        if (ok) {
-            const float4 *src = reinterpret_cast<const float4 *>(
-                b.partials + ((((size_t)(tg * J) * TPG + tl) * NG + g) * kGroupRows + c) * 16 + 4 * q);
-            float4 part[kBatchMaxJ];
+        for (int i = 0; i < IPB; ++i) {
+            const int e = e0 + i * NT;
+            const int q = e & 3, c = (e >> 2) % kGroupRows, g = (e / (4 * kGroupRows)) % NG, tl = e / (4 * kGroupRows * NG);
+            const int t = tg * TPG + tl;
+            const int erow = a.row0 + g * kGroupRows + c;
+            ok[i] = e < ITEMS && erow < a.row0 + a.rows && t < a.n_tiles;
+            h4[i] = float4{0.f, 0.f, 0.f, 0.f};
+            if (ok[i]) {
+                const unsigned long long *src = reinterpret_cast<const unsigned long long *>(
+                    b.partials + ((((size_t)(tg * J) * TPG + tl) * NG + g) * kGroupRows + c) * 16 + 4 * q);
 #pragma unroll
-            for (int jj = 0; jj < kBatchMaxJ; ++jj)           // all loads in flight together
-                part[jj] = jj < J ? src[(size_t)jj * TPG * NG * kGroupRows * 4] : float4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int jj = 0; jj < kBatchMaxJ; ++jj) {         // slice order: the same sum in every run
-                sum.x += part[jj].x; sum.y += part[jj].y; sum.z += part[jj].z; sum.w += part[jj].w;
-            }
-            const float sc = inv_s[erow];
-            sum.x *= sc; sum.y *= sc; sum.z *= sc; sum.w *= sc;
-        }
-        float v[4] = {sum.x, sum.y, sum.z, sum.w};
-        if (EPI == EPI_SWIGLU) {
-            // rows 0..7 of a tile are gate features (q = 0, 1), rows 8..15 the matching up features (q = 2, 3)
-            float out4[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float up = __shfl_down(v[i], 2, 4);
-                out4[i] = v[i] / (1.0f + expf(-v[i])) * up;
-            }
-            if (ok && q < 2) {
-                union { uint2 u; uint16_t h[4]; } term[kTerms];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    uint16_t t3[kTerms];
-                    split3(out4[i], t3);
-#pragma unroll
-                    for (int x = 0; x < kTerms; ++x) term[x].h[i] = t3[x];
-                }
-#pragma unroll
-                for (int x = 0; x < kTerms; ++x)              // 4 consecutive features stay inside one 8-element lane slot
-                    *reinterpret_cast<uint2 *>(a.Xout + xpack_index(erow, t * 8 + 4 * q, a.KS_out, x)) = term[x].u;
-            }
-        } else {
-            const int col = t * 16 + 4 * q;
-            if (EPI == EPI_STORE) {
-                if (ok) *reinterpret_cast<float4 *>(a.Y + (size_t)erow * a.ldy + col) = sum;
-            } else {
-                float sq = 0.f;
-                if (ok) {
-                    float4 h4 = *reinterpret_cast<const float4 *>(a.Y + (size_t)erow * a.ldy + col);
-                    h4.x += v[0]; h4.y += v[1]; h4.z += v[2]; h4.w += v[3];
-                    *reinterpret_cast<float4 *>(a.Y + (size_t)erow * a.ldy + col) = h4;
-                    sq = (h4.x * h4.x + h4.y * h4.y) + (h4.z * h4.z + h4.w * h4.w);
-                    if (a.gain_next) {
-                        const float4 gn = *reinterpret_cast<const float4 *>(a.gain_next + col);
-                        const float y4[4] = {h4.x * gn.x, h4.y * gn.y, h4.z * gn.z, h4.w * gn.w};
-                        union { uint2 u; uint16_t h[4]; } term[kTerms];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            uint16_t t3[kTerms];
-                            split3(y4[i], t3);
-#pragma unroll
-                            for (int x = 0; x < kTerms; ++x) term[x].h[i] = t3[x];
-                        }
-#pragma unroll
-                        for (int x = 0; x < kTerms; ++x)
-                            *reinterpret_cast<uint2 *>(a.Xnext + xpack_index(erow, col, a.n_tiles / 2, x)) = term[x].u;
+                for (int jj = 0; jj < kBatchMaxJ; ++jj) {
+                    if (jj < J) {                             // workgroup-uniform
+                        const unsigned long long *pj = src + (size_t)jj * TPG * NG * kGroupRows * 8;
+                        lo[i][jj] = __hip_atomic_load(pj, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        hi[i][jj] = __hip_atomic_load(pj + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
                 }
-                sq += __shfl_xor(sq, 2);
-                sq += __shfl_xor(sq, 1);
-                if (a.ssq_out && q == 0 && ok) a.ssq_out[(size_t)erow * a.n_tiles + t] = sq;
+                if (EPI == EPI_RESIDUAL) h4[i] = *reinterpret_cast<const float4 *>(a.Y + (size_t)erow * a.ldy + t * 16 + 4 * q);
+            }
+        }
+        if (e0 == (int)threadIdx.x) {
+            // 1 / rms of every input row of this pass from the producer's partial sums: 16 lanes per row, fixed order
+            if (a.ssq_in) {
+                for (int row = a.row0 + (int)threadIdx.x / 16; row < a.row0 + kMaxRows; row += NT / 16) {
+                    const bool in = row < a.row0 + a.rows;
+                    const float inv = rms_inv_from_parts(a.ssq_in + (size_t)(in ? row : a.row0) * (KS * 2), a.ssq_in_parts, lane & 15, in, a.inv_d, a.eps);
+                    if (in && (lane & 15) == 0) inv_s[row] = inv;
+                }
+            } else if (threadIdx.x < kMaxRows) {
+                inv_s[threadIdx.x] = 1.0f;
+            }
+            __syncthreads();
+        }
+#pragma unroll
+        for (int i = 0; i < IPB; ++i) {
+            const int e = e0 + i * NT;
+            const int q = e & 3, c = (e >> 2) % kGroupRows, g = (e / (4 * kGroupRows)) % NG, tl = e / (4 * kGroupRows * NG);
+            const int t = tg * TPG + tl;
+            const int erow = a.row0 + g * kGroupRows + c;
+            float4 sum = float4{0.f, 0.f, 0.f, 0.f};
+            if (ok[i]) {
+#pragma unroll
+                for (int jj = 0; jj < kBatchMaxJ; ++jj) {     // slice order: the same sum in every run
+                    if (jj < J) {
+                        sum.x += __uint_as_float((unsigned)lo[i][jj]); sum.y += __uint_as_float((unsigned)(lo[i][jj] >> 32));
+                        sum.z += __uint_as_float((unsigned)hi[i][jj]); sum.w += __uint_as_float((unsigned)(hi[i][jj] >> 32));
+                    }
+                }
+                const float sc = inv_s[erow];
+                sum.x *= sc; sum.y *= sc; sum.z *= sc; sum.w *= sc;
+            }
+            float v[4] = {sum.x, sum.y, sum.z, sum.w};
+            if (EPI == EPI_SWIGLU) {
+                // rows 0..7 of a tile are gate features (q = 0, 1), rows 8..15 the matching up features (q = 2, 3)
+                float out4[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const float up = __shfl_down(v[x], 2, 4);
+                    out4[x] = v[x] / (1.0f + expf(-v[x])) * up;
+                }
+                if (ok[i] && q < 2) {
+                    union { uint2 u; uint16_t h[4]; } term[kTerms];
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        uint16_t t3[kTerms];
+                        split3(out4[x], t3);
+#pragma unroll
+                        for (int y = 0; y < kTerms; ++y) term[y].h[x] = t3[y];
+                    }
+#pragma unroll
+                    for (int y = 0; y < kTerms; ++y)          // 4 consecutive features stay inside one 8-element lane slot
+                        *reinterpret_cast<uint2 *>(a.Xout + xpack_index(erow, t * 8 + 4 * q, a.KS_out, y)) = term[y].u;
+                }
+            } else {
+                const int col = t * 16 + 4 * q;
+                if (EPI == EPI_STORE) {
+                    if (ok[i]) *reinterpret_cast<float4 *>(a.Y + (size_t)erow * a.ldy + col) = sum;
+                } else {
+                    float sq = 0.f;
+                    if (ok[i]) {
+                        float4 hn = h4[i];
+                        hn.x += v[0]; hn.y += v[1]; hn.z += v[2]; hn.w += v[3];
+                        *reinterpret_cast<float4 *>(a.Y + (size_t)erow * a.ldy + col) = hn;
+                        sq = (hn.x * hn.x + hn.y * hn.y) + (hn.z * hn.z + hn.w * hn.w);
+                        if (a.gain_next) {
+                            const float4 gn = *reinterpret_cast<const float4 *>(a.gain_next + col);
+                            const float y4[4] = {hn.x * gn.x, hn.y * gn.y, hn.z * gn.z, hn.w * gn.w};
+                            union { uint2 u; uint16_t h[4]; } term[kTerms];
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) {
+                                uint16_t t3[kTerms];
+                                split3(y4[x], t3);
+#pragma unroll
+                                for (int y = 0; y < kTerms; ++y) term[y].h[x] = t3[y];
+                            }
+#pragma unroll
+                            for (int y = 0; y < kTerms; ++y)
+                                *reinterpret_cast<uint2 *>(a.Xnext + xpack_index(erow, col, a.n_tiles / 2, y)) = term[y].u;
+                        }
+                    }
+                    sq += __shfl_xor(sq, 2);
+                    sq += __shfl_xor(sq, 1);
+                    if (a.ssq_out && q == 0 && ok[i]) a.ssq_out[(size_t)erow * a.n_tiles + t] = sq;
+                }
             }
         }
     }
@@ -661,7 +703,7 @@ __global__ __launch_bounds__(kBatchWaves * 64) void gemm_batch_kernel(GemmKernel
 
 template <int NG, int TT>
 static hipError_t launch_batch(const GemmKernelArgs &k, const BatchArgs &b, int epilogue, int grid, hipStream_t stream) {
-    dim3 g(grid), block(kBatchWaves * 64);
+    dim3 g(grid), block((kBatchWaves + kBatchLoaders) * 64);
     switch (epilogue) {
         case EPI_STORE: hipLaunchKernelGGL((gemm_batch_kernel<NG, TT, EPI_STORE>), g, block, 0, stream, k, b); break;
         case EPI_RESIDUAL: hipLaunchKernelGGL((gemm_batch_kernel<NG, TT, EPI_RESIDUAL>), g, block, 0, stream, k, b); break;
@@ -891,16 +933,17 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStre
         SPD_GEMM_CASE(1, 16, 8);
     }
 #undef SPD_GEMM_CASE
-    // More than 10 rows with a scratch buffer: the tile-splitting kernel makes one pass over the weights for up to 13
-    // row groups (65 rows).  Measured at the 7B shapes: beyond 40 rows it always wins (the K-splitting kernel
-    // needs two passes there); at 21..40 rows it wins for the long or wide matrices (down: 38 against 52 us,
-    // gate|up: 62 against 67, LM head: 80 against 91) and loses for QKV and O (50 against 40, 26 against 24);
-    // up to 20 rows the K-splitting kernel is faster everywhere.
-    const bool batch_pays = groups > 8 || (groups > 4 && (k.KS > 128 || k.n_tiles >= 1024));
-    if (a.batch_partials && a.batch_arrive && groups > 2 && !tune.no_batch && (batch_pays || tune.force_batch)) {
+    // More than 20 rows with a scratch buffer: the tile-splitting kernel makes one pass over the weights for up to 13
+    // row groups (65 rows).  Measured at the 7B shapes and 40 rows: gate|up 52 against 67 us for the K-splitting
+    // kernel, down 41 against 52, LM head 59 against 91, QKV and O the same (40 and 23); beyond 40 rows the
+    // K-splitting kernel needs a second pass; up to 20 rows it is the faster one (4.5 against 5.1 ms per step).
+    const bool batch_pays = groups > 4;
+    if (a.batch_partials && a.batch_arrive && a.batch_zero && groups > 2 && !tune.no_batch && (batch_pays || tune.force_batch)) {
         const int NG = groups <= 4 ? 4 : (groups <= 8 ? 8 : kMaxGroups);
-        const BatchPlan p = batch_plan(k.n_tiles, k.KS, NG);
-        BatchArgs b{a.batch_partials, a.batch_arrive, p.J};
+        BatchPlan p = batch_plan(k.n_tiles, k.KS, NG);
+        if (tune.grid_cap > 0 && tune.grid_cap / p.n_tgroups < p.J)          // a cap on the grid means fewer K slices here
+            p.J = tune.grid_cap / p.n_tgroups > 0 ? tune.grid_cap / p.n_tgroups : 1;
+        BatchArgs b{a.batch_partials, a.batch_arrive, p.J, (const uint4 *)a.batch_zero};
         const int bgrid = p.n_tgroups * p.J;
 #define SPD_BATCH_CASE(NG_, TT_) if (NG == NG_ && p.TT == TT_) return launch_batch<NG_, TT_>(k, b, epilogue, bgrid, stream)
         SPD_BATCH_CASE(4, 1); SPD_BATCH_CASE(4, 2);

@@ -64,6 +64,7 @@ struct GemmArgs {
     // groups' arrival counters (1024 entries, zero between launches); NULL: the kernels that need neither
     float *batch_partials;
     unsigned *batch_arrive;
+    const void *batch_zero;   // 1 KiB of zeros that nobody writes
 };
 size_t gemm_batch_scratch_bytes(int N, int K);
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStream_t stream);

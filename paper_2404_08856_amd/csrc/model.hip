@@ -50,7 +50,7 @@ struct Layout {                    // byte offsets inside the three buffers
     size_t kv_layer_stride, kv_k_bytes, kv_v_bytes, kv_total;
     int v_stride;
     // workspace
-    size_t h, qkv, xn, xo, xf, rope, logits, ssq_a, ssq_b, d_lens, d_error, qa_count, qa_abort, part, arrive, ws_total;
+    size_t h, qkv, xn, xo, xf, rope, logits, ssq_a, ssq_b, d_lens, d_error, qa_count, qa_abort, part, arrive, zero, ws_total;
 };
 
 int32_t check_shape(const spd_model_config &c) {
@@ -113,6 +113,7 @@ void make_layout(const spd_model_config &c, Layout &L) {
         pb = b > pb ? b : pb;
     L.part = take(pb);
     L.arrive = take(1024 * 4);
+    L.zero = take(1024);
     L.ws_total = off;
 }
 
@@ -478,7 +479,7 @@ int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const flo
         at.k_cache = kv_l + (size_t)seq0 * c.n_heads * c.max_positions * c.head_dim * 2;
         at.v_cache = kv_l + align_up(L.kv_k_bytes, 256) + (size_t)seq0 * c.n_heads * c.head_dim * L.v_stride * 2;
         GemmArgs g{};
-        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive);
+        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive); g.batch_zero = m->ws + L.zero;
         if (fused) {
             QkvAttnArgs qa{};
             qa.W = m->packed + L.wqkv[l]; qa.X = xn; qa.K = d; qa.rows = rows;
@@ -498,24 +499,24 @@ int32_t forward(spd_model *m, const int32_t *tokens, int token_stride, const flo
             }
         }
         g = GemmArgs{};
-        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive);
+        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive); g.batch_zero = m->ws + L.zero;
         g.W = m->packed + L.wo[l]; g.X = xo; g.N = d; g.K = HD; g.rows = rows; g.Y = h; g.ldy = d;
         g.gain_next = gain_of(L.mlp_norm[l]); g.Xnext = xn; g.ssq_out = ssq_a;
         PROF_GEMM(PK_O, launch_gemm(g, EPI_RESIDUAL, m->t_o, st));
         g = GemmArgs{};
-        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive);
+        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive); g.batch_zero = m->ws + L.zero;
         g.W = m->packed + L.wgu[l]; g.X = xn; g.N = 2 * F; g.K = d; g.rows = rows; g.Xout = xf; g.K_out = F;
         g.ssq_in = ssq_a; g.ssq_in_parts = d_tiles; g.eps = c.rms_eps;
         PROF_GEMM(PK_GATE_UP, launch_gemm(g, EPI_SWIGLU, m->t_gu, st));
         g = GemmArgs{};
-        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive);
+        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive); g.batch_zero = m->ws + L.zero;
         g.W = m->packed + L.wdown[l]; g.X = xf; g.N = d; g.K = F; g.rows = rows; g.Y = h; g.ldy = d;
         g.gain_next = gain_of(l + 1 < c.n_layers ? L.attn_norm[l + 1] : L.final_norm); g.Xnext = xn; g.ssq_out = ssq_b;
         PROF_GEMM(PK_DOWN, launch_gemm(g, EPI_RESIDUAL, m->t_down, st));
     }
     if (logits_out) {
         GemmArgs g{};
-        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive);
+        g.batch_partials = (float *)(m->ws + L.part); g.batch_arrive = (unsigned *)(m->ws + L.arrive); g.batch_zero = m->ws + L.zero;
         g.W = m->packed + L.lm_head; g.X = xn; g.N = V; g.K = d; g.rows = rows; g.Y = logits_out; g.ldy = V;
         g.ssq_in = ssq_b; g.ssq_in_parts = d_tiles; g.eps = c.rms_eps;
         PROF_GEMM(PK_LM_HEAD, launch_gemm(g, EPI_STORE, m->t_lm, st));
