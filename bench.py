@@ -39,6 +39,10 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="time call-by-call launches only (no graph capture of the step)")
     ap.add_argument("--no-side-configs", action="store_true", help="skip the draft-step and accept-kernel timings")
     ap.add_argument("--cpu-reps", type=int, default=3, help="timed repetitions of the oracle's verify step (after one warm-up)")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="sequences verified per step (each with its own real prefix); other than 1 is a side workload, marked as such")
+    ap.add_argument("--probes", action="store_true",
+                    help="also time plain read kernels: one of 1 GiB, and a chain with the sizes of one layer's projections")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="after the timed region, run this many plain 1 GiB device copies (reference dispatches of known "
@@ -459,6 +463,23 @@ def full_loop(args, spd, synth, torch, n_seqs=8, n_text=1472, n_new=256, gammas=
     return res
 
 
+def read_probes(shape, spd, torch):
+    """What the device gives kernels that only read: one large kernel, and the chain of one layer's projection sizes."""
+    HD = shape.n_heads * shape.head_dim
+    layer = [3 * HD * shape.d_model * 2, shape.d_model * HD * 2, 2 * shape.d_ffn * shape.d_model * 2, shape.d_model * shape.d_ffn * 2]
+    buf = torch.empty(3 << 30, dtype=torch.uint8, device="cuda").random_(0, 256)
+    big, _ = spd.spd_probe_read_chain(buf, [1 << 30], reps=10)
+    us, chain = spd.spd_probe_read_chain(buf, layer * 4, reps=10)
+    per_stage = [sum(us[i::4]) / 4 for i in range(4)]
+    del buf
+    torch.cuda.empty_cache()
+    return {"read_1GiB": {"us": big[0], "GBps": (1 << 30) / big[0] / 1e3},
+            "layer_chain": {"stage_bytes": layer, "kernel_us": per_stage,
+                            "kernel_GBps": [b / t / 1e3 for b, t in zip(layer, per_stage)],
+                            "us_per_layer_kernels_only": sum(per_stage), "us_per_layer_wall": chain / 4,
+                            "wall_GBps": sum(layer) / (chain / 4) / 1e3}}
+
+
 def batched_verify(args, spd, synth, torch):
     """The 7B verify step for several sequences at once (rows = sequences x (gamma + 1) span several row groups)."""
     M = args.gamma + 1
@@ -527,39 +548,42 @@ def main():
     M = args.gamma + 1
     shape = synth.SHAPES["llama7b"] if args.layers <= 0 else synth.llama7b_layers(args.layers)
     n_prefix = args.image_rows + args.text_tokens
-    cfg = spd.make_config(shape, 1, n_prefix + M + 3)
+    B = args.batch
+    cfg = spd.make_config(shape, B, n_prefix + M + 3)
 
     t0 = time.time()
     w = synth.make_weights(shape, args.seed, device="cuda")
     model = spd.Model(cfg, w)
     w_host = None
-    if not args.no_cpu_baseline:                 # host copy (bf16 bits) of the very weights the GPU runs, for the oracle
+    if not args.no_cpu_baseline and B == 1:      # host copy (bf16 bits) of the very weights the GPU runs, for the oracle
         w_host = synth.weights_to_numpy(w)
     del w
     torch.cuda.empty_cache()
     print(f"[bench] model built in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
 
     # KV cache: 576 image-position embeddings ~ N(0,1), then 64 text tokens
-    img = torch.from_numpy(synth.image_rows(args.image_rows, shape.d_model, args.seed)).cuda()
-    text = torch.from_numpy(synth.text_tokens(args.text_tokens, shape.vocab, args.seed)).cuda()
-    model.spd_prefill(0, img)
-    model.spd_prefill_tokens(0, text)
-    assert model.spd_kv_get_len(1) == [n_prefix]
+    for b in range(B):                           # sequence 0 is the headline's; further ones (--batch) get prefixes of their own
+        img = torch.from_numpy(synth.image_rows(args.image_rows, shape.d_model, args.seed + 100 * b)).cuda()
+        text = torch.from_numpy(synth.text_tokens(args.text_tokens, shape.vocab, args.seed + 100 * b)).cuda()
+        model.spd_prefill(b, img)
+        model.spd_prefill_tokens(b, text)
+    assert model.spd_kv_get_len(B) == [n_prefix] * B
 
-    vt = torch.from_numpy(synth.text_tokens(M, shape.vocab, args.seed + 1)).cuda()[None].contiguous()
-    logits = torch.empty((1, M, shape.vocab), dtype=torch.float32, device="cuda")
+    vt = torch.from_numpy(synth.text_tokens(B * M, shape.vocab, args.seed + 1).reshape(B, M)).cuda().contiguous()
+    logits = torch.empty((B, M, shape.vocab), dtype=torch.float32, device="cuda")
     model.spd_verify_forward(vt, logits)
     # synthetic draft rows: target logits + N(0, 1) noise, draft tokens drawn from them
     g = torch.Generator(device="cuda").manual_seed(args.seed + 2)
-    draft_logits = (logits[:, :args.gamma] + torch.randn((1, args.gamma, shape.vocab), generator=g, device="cuda")).contiguous()
-    draft_tokens = torch.multinomial(torch.softmax(draft_logits[0], -1), 1, generator=g).to(torch.int32).reshape(1, args.gamma)
-    u = torch.from_numpy(synth.uniforms((1, M), args.seed + 3)).cuda()
-    k_out = torch.empty(1, dtype=torch.int32, device="cuda")
-    y_out = torch.empty(1, dtype=torch.int32, device="cuda")
-    acc_ws = torch.empty(spd.spd_accept_workspace_bytes(1, args.gamma, shape.vocab), dtype=torch.uint8, device="cuda")
+    draft_logits = (logits[:, :args.gamma] + torch.randn((B, args.gamma, shape.vocab), generator=g, device="cuda")).contiguous()
+    draft_tokens = torch.multinomial(torch.softmax(draft_logits.reshape(B * args.gamma, -1), -1), 1,
+                                     generator=g).to(torch.int32).reshape(B, args.gamma)
+    u = torch.from_numpy(synth.uniforms((B, M), args.seed + 3)).cuda()
+    k_out = torch.empty(B, dtype=torch.int32, device="cuda")
+    y_out = torch.empty(B, dtype=torch.int32, device="cuda")
+    acc_ws = torch.empty(spd.spd_accept_workspace_bytes(B, args.gamma, shape.vocab), dtype=torch.uint8, device="cuda")
 
     def step():
-        model.spd_kv_set_len([n_prefix])            # roll the KV length back: every step verifies at the same context
+        model.spd_kv_set_len([n_prefix] * B)        # roll the KV length back: every step verifies at the same context
         model.spd_verify_forward(vt, logits)
         spd.spd_speculative_accept(logits, draft_logits, draft_tokens, u, 1.0, 0, k_out, y_out, None, acc_ws)
 
@@ -635,14 +659,14 @@ def main():
 
     HD = shape.n_heads * shape.head_dim
     weight_bytes = shape.streamed_weight_bytes()
-    kv_bytes = shape.n_layers * 2 * (n_prefix + M) * HD * 2
-    accept_bytes = (2 * args.gamma + 1) * shape.vocab * 4
+    kv_bytes = B * shape.n_layers * 2 * (n_prefix + M) * HD * 2
+    accept_bytes = B * (2 * args.gamma + 1) * shape.vocab * 4
     step_bytes = weight_bytes + kv_bytes + accept_bytes
     gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     per_kind_bytes = {"qkv": 3 * HD * shape.d_model * 2, "o": shape.d_model * HD * 2, "gate_up": 2 * shape.d_ffn * shape.d_model * 2,
                       "down": shape.d_model * shape.d_ffn * 2, "lm_head": shape.vocab * shape.d_model * 2,
-                      "attention": 2 * (n_prefix + M) * HD * 2}
+                      "attention": B * 2 * (n_prefix + M) * HD * 2}
     for k, b in per_kind_bytes.items():
         if kinds[k]["ms_per_launch"]:
             kinds[k]["GBps"] = b / (kinds[k]["ms_per_launch"] * 1e-3) / 1e9
@@ -653,26 +677,28 @@ def main():
 
     out = {
         "metric": "7B verify-step verified tokens/sec (gamma=4), with achieved HBM GB/s",
-        "value": M / (ms_per_step * 1e-3),
+        "value": B * M / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "llama7b_verify_step: 32 layers d=4096 32x128 heads ffn 11008 vocab 32000, bf16 N(0,0.02) weights, "
-                               f"KV prefix {args.image_rows} image rows + {args.text_tokens} text tokens, gamma+1={M} tokens, batch 1, "
+                               f"KV prefix {args.image_rows} image rows + {args.text_tokens} text tokens, gamma+1={M} tokens, batch {B}, "
                                "then speculative accept (logit inputs, temperature 1)",
-                   "n_layers": shape.n_layers, "gamma": args.gamma, "prefix_positions": n_prefix, "batch": 1},
+                   "n_layers": shape.n_layers, "gamma": args.gamma, "prefix_positions": n_prefix, "batch": B},
         "launch": launch, "ms_per_step_eager": eager_ms, "ms_per_step_graph": graph_ms,
         "hbm_GBps": gbps, "hbm_frac_of_peak": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_step": step_bytes,
         "roofline": {"bound": "hbm", "kernel": dom_name,
                      "achieved": dom_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": dom_gbps / HBM_PEAK_GBPS,
-                     "traffic": GATE_UP_7B_TRAFFIC_BYTES if (dom == "gate_up" and args.layers <= 0) else None,
+                     "traffic": GATE_UP_7B_TRAFFIC_BYTES if (dom == "gate_up" and args.layers <= 0 and B == 1) else None,
                      "bytes_per_launch": dom_bytes, "ms_per_launch": dom_ms},
         "kernels": kinds,
     }
     if not args.no_side_configs:
         out["other_configs"] = side_configs(args, spd, synth, torch)
+    if args.probes:
+        out["read_probes"] = read_probes(shape, spd, torch)
     if args.calib_copy > 0:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
@@ -681,9 +707,11 @@ def main():
         torch.cuda.synchronize()
     if args.layers > 0:
         out["invalid"] = "development run with fewer layers than the 7B shape"
+    if B != 1:
+        out["invalid"] = "side workload (several sequences per step), not the headline configuration"
     if not device_ok:
         out["invalid"] = "a device-side wait gave up during the run (spd_device_status): results are not valid"
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and B == 1:
         kv_host = []
         kbuf = torch.empty((n_prefix, shape.n_heads, shape.head_dim), dtype=torch.float32, device="cuda")
         vbuf = torch.empty_like(kbuf)

@@ -124,6 +124,7 @@ typedef struct {
     int32_t  gemm_waves[SPD_N_PROJECTIONS];          /* waves per workgroup: 4, 8 or 16; 0 = default */
     int32_t  gemm_grid_cap[SPD_N_PROJECTIONS];       /* upper bound of the grid; 0 = default         */
     int32_t  gemm_general_kernel[SPD_N_PROJECTIONS]; /* 1: never the register-resident variant       */
+    int32_t  gemm_ring[SPD_N_PROJECTIONS];           /* general kernel: weight blocks a wave keeps in flight, 8 or 16; 0 = default */
     int32_t  batch_kernel;           /* calls of more than 10 rows: 0 = the library chooses per projection between the
                                         tile-splitting batched kernel (one pass over the weights for up to 64 rows) and
                                         the K-splitting kernels (passes of 40 rows); 1 = always the former, 2 = always
@@ -302,6 +303,16 @@ int32_t spd_device_status(spd_model *model, void *stream);
 #define SPD_TRACE_KINDS 7
 int32_t spd_trace_enable(spd_model *model, int32_t enable);
 int32_t spd_trace_read(spd_model *model, int32_t n_kinds, double *h_ms_sum, int32_t *h_count);
+
+/* Measurement aid (not part of the method): launches n_stages plain streaming-read kernels back to back on
+ * `stream`, stage i reading h_stage_bytes[i] bytes (multiples of 1024) of `buffer` (any readable device memory
+ * of buffer_bytes >= the sum; consecutive repetitions read different windows of it), `reps` times, and reports
+ * in microseconds each kernel's own execution time (mean over the repetitions) and the wall time of one chain
+ * (events around all repetitions).  This is what a chain of kernels of the projections' sizes costs on the
+ * device when the kernels do nothing but read.  `sink`: 4 KiB of device memory the kernels may write.  Blocks
+ * the host.  Errors: SPD_ERR_INVALID_ARG, SPD_ERR_CAPACITY (buffer too small / misaligned), SPD_ERR_HIP. */
+int32_t spd_probe_read_chain(const void *buffer, size_t buffer_bytes, const size_t *h_stage_bytes, int32_t n_stages,
+                             int32_t reps, void *sink, double *h_kernel_us, double *h_chain_us_per_rep, void *stream);
 
 #ifdef __cplusplus
 }

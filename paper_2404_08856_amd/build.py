@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspd.so")
-SOURCES = ["gemm.hip", "rowwise.hip", "attention.hip", "qkv_attention.hip", "sampler.hip", "model.hip"]
+SOURCES = ["gemm.hip", "rowwise.hip", "attention.hip", "qkv_attention.hip", "sampler.hip", "probe.hip", "model.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

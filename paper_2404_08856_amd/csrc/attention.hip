@@ -15,12 +15,14 @@ hipError_t launch_attention(const AttnArgs &a, hipStream_t stream) {
     if (a.Mq < 1 || a.Mq > 8 || a.m0 < 0 || a.m0 + a.Mq > a.M || a.M > a.max_positions) return hipErrorInvalidValue;
     // Workgroups per head (slices of the head dimension).  One sequence: 16 output dimensions per
     // workgroup is fastest at the 7B shape (15.4 us per layer against 16.2 with 32 and 18.8 with 64).
-    // More (sequence, head) pairs: every slice re-reads K, so as soon as the pairs alone fill the
-    // chip the slices only cost (8 sequences, context 2048: 73 us per layer unsliced, 76 with 2,
-    // 108 with 4, 160 with 8 slices).  a.slices (a tuning knob for tests and sweeps) overrides for head_dim 128.
+    // More (sequence, head) pairs: every slice re-reads K, so slices beyond one workgroup per CU only
+    // cost (8 sequences, context 2048: 73 us per layer unsliced, 76 with 2, 108 with 4, 160 with 8 slices;
+    // context 640, 5 queries, 32 heads: 3 sequences 17.8 us with 2 slices against 24.2 with 4, 5 sequences
+    // 22.3 unsliced against 28.9 with 2): the largest count that keeps pairs * slices within the 256 CUs.
+    // a.slices (a tuning knob for tests and sweeps) overrides for head_dim 128.
     int slices = a.slices;
     const int pairs = a.n_seqs * a.H;
-    if (slices != 1 && slices != 2 && slices != 4 && slices != 8) slices = pairs >= 256 ? 1 : (pairs >= 128 ? 2 : (pairs >= 64 ? 4 : 8));
+    if (slices != 1 && slices != 2 && slices != 4 && slices != 8) slices = pairs > 128 ? 1 : (pairs > 64 ? 2 : (pairs > 32 ? 4 : 8));
     if (slices == 1 && a.Mq > kGroupRows) slices = 2;   // two query groups and a whole head do not fit the registers
     // up to 5 queries per sequence: one query group; 6..8: two groups share the cached keys' registers
 #define SPD_ATTN(DH_, DS_, AW_)                                                                                              \

@@ -150,8 +150,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs 
         const int erow = a.row0 + eg * kGroupRows + em;               // absolute row of the call
         const bool e_in = e < NG * 128 && em < kGroupRows && erow < a.row0 + a.rows;
         const bool e_active = (EPI != EPI_SWIGLU) ? e_in : (e_in && en < 8);
-        float hold = 0.f;
-        if (EPI == EPI_RESIDUAL && e_active) hold = a.Y[(size_t)erow * a.ldy + (size_t)t * 16 + en];
+        float hold = 0.f, gnext = 0.f;
+        if (EPI == EPI_RESIDUAL && e_active) {
+            hold = a.Y[(size_t)erow * a.ldy + (size_t)t * 16 + en];
+            if (a.gain_next) gnext = a.gain_next[t * 16 + en];
+        }
 
         f32x4_t acc[NG];
 #pragma unroll
@@ -233,7 +236,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(GemmKernelArgs 
                     a.Y[(size_t)erow * a.ldy + col] = hnew;
                     if (a.gain_next) {
                         uint16_t t3[kTerms];
-                        split3(hnew * a.gain_next[col], t3);
+                        split3(hnew * gnext, t3);
                         const int KSn = a.n_tiles / 2;               // N / 32
 #pragma unroll
                         for (int q = 0; q < kTerms; ++q) a.Xnext[xpack_index(erow, col, KSn, q)] = t3[q];
@@ -401,37 +404,42 @@ static hipError_t launch_multi(const GemmKernelArgs &k, int epilogue, int grid, 
 // the epilogue, then clears the counter for the next launch.  Fixed order => bit-reproducible.  The partials
 // cross workgroups (and XCDs, each with its own L2) inside one launch: device-scope stores, acknowledged
 // before the arrival is counted, and device-scope loads.
-constexpr int kBatchWaves = 8, kBatchMaxJ = 4;
+constexpr int kBatchWaves = 8, kBatchMaxJ = 8;
 constexpr int kBatchCH = 4;      // K-steps per activation chunk: two LDS buffers of NG * CH KiB each
 // chunks the weight ring runs ahead (registers: TT * RDC * CH * 4 for the ring next to TT * NG * 4 accumulators)
 constexpr int batch_ring_chunks(int NG, int TT) { return (TT * NG * 4 + TT * 2 * kBatchCH * 4 <= 144) ? 2 : 1; }
 
 struct BatchPlan { int TT, J, n_tgroups; };
-// TT tiles per wave (2 where the matrix has the tiles for it; accumulators = TT * NG * 4 VGPRs, weight ring
-// = TT * CH blocks in flight per wave); J K-slices (at most 4: the last arriver reads J partials per
-// output) so that there is about one workgroup per CU.
-static BatchPlan batch_plan(int n_tiles, int KS, int NG) {
+// TT tiles per wave (accumulators = TT * NG * 4 VGPRs, weight ring = TT * CH blocks in flight per wave); J K-slices (at most 8: the last arriver reads J partials per
+// output) so that there is about one workgroup per CU: the J in range with the shortest longest slice.
+static BatchPlan batch_plan(int n_tiles, int KS, int NG, int tt = 0) {
     BatchPlan p;
-    p.TT = n_tiles >= 512 ? 2 : 1;
+    // Measured at the 7B shapes: one tile per wave beats two everywhere (40 rows: 5.31 against 5.45 ms per step, 20 rows:
+    // 4.02 against 4.27) -- twice the workgroups, and the larger matrices then need no K slices at all.  Two tiles per
+    // wave remain for matrices with more tile groups than arrival counters.
+    p.TT = tt == 1 || tt == 2 ? tt : 1;
     p.n_tgroups = (n_tiles + kBatchWaves * p.TT - 1) / (kBatchWaves * p.TT);
     const int unit = batch_ring_chunks(NG, p.TT) * kBatchCH;
     const int n_units = (KS + unit - 1) / unit;
-    int J = 256 / p.n_tgroups;                                // at most one workgroup per CU: a single round
-    if (J > kBatchMaxJ) J = kBatchMaxJ;
-    if (J > n_units) J = n_units;
-    if (J < 1) J = 1;
-    while (J > 1 && n_units % J != 0 && n_units / J < 8) --J;     // short slices: only equal ones
+    int Jmax = 256 / p.n_tgroups;                             // at most one workgroup per CU: a single round
+    if (Jmax > kBatchMaxJ) Jmax = kBatchMaxJ;
+    if (Jmax > n_units) Jmax = n_units;
+    if (Jmax < 1) Jmax = 1;
+    int J = 1;
+    for (int c = 2; c <= Jmax; ++c)                           // slices are whole units: the longest one has ceil(n_units / c)
+        if ((n_units + c - 1) / c < (n_units + J - 1) / J) J = c;
     p.J = J;
     return p;
 }
 size_t gemm_batch_scratch_bytes(int N, int K) {
     const int n_tiles = N / 16, KS = (K + 31) / 32;
     size_t worst = 0;
-    for (int NG : {8, kMaxGroups}) {
-        const BatchPlan p = batch_plan(n_tiles, KS, NG);
-        const size_t b = (size_t)p.J * p.n_tgroups * kBatchWaves * p.TT * NG * 80 * sizeof(float);
-        worst = b > worst ? b : worst;
-    }
+    for (int NG : {4, 8, kMaxGroups})
+        for (int tt : {1, 2}) {
+            const BatchPlan p = batch_plan(n_tiles, KS, NG, tt);
+            const size_t b = (size_t)p.J * p.n_tgroups * kBatchWaves * p.TT * NG * 80 * sizeof(float);
+            worst = b > worst ? b : worst;
+        }
     return worst;
 }
 
@@ -562,22 +570,22 @@ __global__ __launch_bounds__((kBatchWaves + kBatchLoaders) * 64) void gemm_batch
         }
     }
     __syncthreads();
-    {
+    if (J > 1) {                                          // (a single slice finishes its tiles straight from the staging area)
         const unsigned long long *src = reinterpret_cast<const unsigned long long *>(stage);
         unsigned long long *dst = reinterpret_cast<unsigned long long *>(b.partials + (size_t)(tg * J + j) * TPG * NG * 80);
         for (int i = threadIdx.x; i < TPG * NG * 40; i += (WAVES + LW) * 64)
             __hip_atomic_store(dst + i, src[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // once the partials are acknowledged, count this workgroup in; the last one to arrive finishes the tiles
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const unsigned ticket = __hip_atomic_fetch_add(b.arrive + tg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            is_last = ticket == (unsigned)(J - 1);
+        }
+        __syncthreads();
+        if (!is_last) return;
+        if (threadIdx.x == 0) __hip_atomic_store(b.arrive + tg, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
     }
-    // once the partials are acknowledged, count this workgroup in; the last one to arrive finishes the tiles
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned ticket = __hip_atomic_fetch_add(b.arrive + tg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        is_last = ticket == (unsigned)(J - 1);
-    }
-    __syncthreads();
-    if (!is_last) return;
-    if (threadIdx.x == 0) __hip_atomic_store(b.arrive + tg, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
 
     // Four columns (tile, group, row slot c, columns 4 q .. 4 q + 3) per thread and item; q fastest: the 16
     // columns of a (row, tile) sit in 4 neighbouring lanes.  The other slices' partials were written through to
@@ -585,9 +593,12 @@ __global__ __launch_bounds__((kBatchWaves + kBatchLoaders) * 64) void gemm_batch
     // before anything is used, and before the rows' 1 / rms is worked out, so the tail costs about two round trips.
     constexpr int NT = (WAVES + LW) * 64;
     constexpr int ITEMS = TPG * NG * kGroupRows * 4;
-    constexpr int IPB = 4;                                    // items in flight per thread
+    // At most 16 partial quads in flight per thread: four items for up to 4 slices, two for up to 8.
+    auto finish = [&](auto jc_, auto ipb_) __attribute__((always_inline)) {
+    constexpr int JC = decltype(jc_)::value > 0 ? decltype(jc_)::value : 1, IPB = decltype(ipb_)::value;
+    constexpr bool LOCAL = decltype(jc_)::value == 0;         // the only slice: its sums are still in the staging area
     for (int e0 = threadIdx.x; e0 - (int)threadIdx.x < ITEMS; e0 += NT * IPB) {
-        unsigned long long lo[IPB][kBatchMaxJ], hi[IPB][kBatchMaxJ];
+        unsigned long long lo[IPB][JC], hi[IPB][JC];
         float4 h4[IPB];
         bool ok[IPB];
 #pragma unroll
@@ -598,11 +609,17 @@ __global__ __launch_bounds__((kBatchWaves + kBatchLoaders) * 64) void gemm_batch
             const int erow = a.row0 + g * kGroupRows + c;
             ok[i] = e < ITEMS && erow < a.row0 + a.rows && t < a.n_tiles;
             h4[i] = float4{0.f, 0.f, 0.f, 0.f};
-            if (ok[i]) {
+            if (ok[i] && LOCAL) {
+                const unsigned long long *src = reinterpret_cast<const unsigned long long *>(
+                    stage + (((size_t)tl * NG + g) * kGroupRows + c) * 16 + 4 * q);
+                lo[i][0] = src[0];
+                hi[i][0] = src[1];
+                if (EPI == EPI_RESIDUAL) h4[i] = *reinterpret_cast<const float4 *>(a.Y + (size_t)erow * a.ldy + t * 16 + 4 * q);
+            } else if (ok[i]) {
                 const unsigned long long *src = reinterpret_cast<const unsigned long long *>(
                     b.partials + ((((size_t)(tg * J) * TPG + tl) * NG + g) * kGroupRows + c) * 16 + 4 * q);
 #pragma unroll
-                for (int jj = 0; jj < kBatchMaxJ; ++jj) {
+                for (int jj = 0; jj < JC; ++jj) {
                     if (jj < J) {                             // workgroup-uniform
                         const unsigned long long *pj = src + (size_t)jj * TPG * NG * kGroupRows * 8;
                         lo[i][jj] = __hip_atomic_load(pj, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -634,7 +651,7 @@ __global__ __launch_bounds__((kBatchWaves + kBatchLoaders) * 64) void gemm_batch
             float4 sum = float4{0.f, 0.f, 0.f, 0.f};
             if (ok[i]) {
 #pragma unroll
-                for (int jj = 0; jj < kBatchMaxJ; ++jj) {     // slice order: the same sum in every run
+                for (int jj = 0; jj < JC; ++jj) {             // slice order: the same sum in every run
                     if (jj < J) {
                         sum.x += __uint_as_float((unsigned)lo[i][jj]); sum.y += __uint_as_float((unsigned)(lo[i][jj] >> 32));
                         sum.z += __uint_as_float((unsigned)hi[i][jj]); sum.w += __uint_as_float((unsigned)(hi[i][jj] >> 32));
@@ -699,6 +716,10 @@ __global__ __launch_bounds__((kBatchWaves + kBatchLoaders) * 64) void gemm_batch
             }
         }
     }
+    };
+    if (J == 1) finish(std::integral_constant<int, 0>{}, std::integral_constant<int, 4>{});
+    else if (J <= 4) finish(std::integral_constant<int, 4>{}, std::integral_constant<int, 4>{});
+    else finish(std::integral_constant<int, kBatchMaxJ>{}, std::integral_constant<int, 2>{});
 }
 
 template <int NG, int TT>
@@ -776,8 +797,11 @@ __global__ __launch_bounds__(WAVES * 64, (NG > 1 ? 1 : (NB <= 8 ? 4 : 2))) void 
         float inv = inv_row[0];
 #pragma unroll
         for (int g = 1; g < NG; ++g) inv = (eg == g) ? inv_row[g] : inv;
-        float hold = 0.f;
-        if (EPI == EPI_RESIDUAL && e_active) hold = a.Y[(size_t)erow * a.ldy + (size_t)t * 16 + en];
+        float hold = 0.f, gnext = 0.f;                    // the epilogue's operands, on their way before the tile's arithmetic
+        if (EPI == EPI_RESIDUAL && e_active) {
+            hold = a.Y[(size_t)erow * a.ldy + (size_t)t * 16 + en];
+            if (a.gain_next) gnext = a.gain_next[t * 16 + en];
+        }
 
         f32x4_t acc[NG];
         const uint4 *wcur = a.W + ((size_t)t * KS + s0) * 64 + lane;
@@ -818,7 +842,7 @@ __global__ __launch_bounds__(WAVES * 64, (NG > 1 ? 1 : (NB <= 8 ? 4 : 2))) void 
                     a.Y[(size_t)erow * a.ldy + col] = hnew;
                     if (a.gain_next) {
                         uint16_t t3[kTerms];
-                        split3(hnew * a.gain_next[col], t3);
+                        split3(hnew * gnext, t3);
                         const int KSn = a.n_tiles / 2;
 #pragma unroll
                         for (int q = 0; q < kTerms; ++q) a.Xnext[xpack_index(erow, col, KSn, q)] = t3[q];
@@ -933,14 +957,16 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStre
         SPD_GEMM_CASE(1, 16, 8);
     }
 #undef SPD_GEMM_CASE
-    // More than 20 rows with a scratch buffer: the tile-splitting kernel makes one pass over the weights for up to 13
-    // row groups (65 rows).  Measured at the 7B shapes and 40 rows: gate|up 52 against 67 us for the K-splitting
-    // kernel, down 41 against 52, LM head 59 against 91, QKV and O the same (40 and 23); beyond 40 rows the
-    // K-splitting kernel needs a second pass; up to 20 rows it is the faster one (4.5 against 5.1 ms per step).
-    const bool batch_pays = groups > 4;
+    // More than 10 rows with a scratch buffer: the tile-splitting kernel makes one pass over the weights for up to 13
+    // row groups (65 rows).  Measured at the 7B shapes against the K-splitting kernel (microseconds per launch), 20 rows:
+    // gate|up 40 / 48, down 28 / 36, LM head 51 / 66, QKV 30 / 29, O 17 / 17; 40 rows: gate|up 51 / 67, down 34 / 52,
+    // LM head 51 / 91, QKV 35 / 40, O 22 / 23; beyond 40 rows the K-splitting kernel needs a second pass.
+    const bool batch_pays = groups > 2;
     if (a.batch_partials && a.batch_arrive && a.batch_zero && groups > 2 && !tune.no_batch && (batch_pays || tune.force_batch)) {
         const int NG = groups <= 4 ? 4 : (groups <= 8 ? 8 : kMaxGroups);
         BatchPlan p = batch_plan(k.n_tiles, k.KS, NG);
+        if (p.n_tgroups > kBatchMaxTileGroups) p = batch_plan(k.n_tiles, k.KS, NG, 2);
+        if (p.n_tgroups > kBatchMaxTileGroups) return hipErrorInvalidValue;     // more than 256 K output columns
         if (tune.grid_cap > 0 && tune.grid_cap / p.n_tgroups < p.J)          // a cap on the grid means fewer K slices here
             p.J = tune.grid_cap / p.n_tgroups > 0 ? tune.grid_cap / p.n_tgroups : 1;
         BatchArgs b{a.batch_partials, a.batch_arrive, p.J, (const uint4 *)a.batch_zero};

@@ -40,6 +40,7 @@ size_t packed_matrix_bytes(int N, int K);
 
 // ---- skinny weight-streaming GEMM -------------------------------------------------
 enum Epilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+constexpr int kBatchMaxTileGroups = 1024;    // arrival counters of the batched projection kernel (one per tile group)
 struct GemmTuning { int waves; int grid_cap; int ring; int no_regb; int no_batch; int force_batch; };   // 0 = default for grid_cap / ring
 struct GemmArgs {
     const void *W;        // packed weights [N, K]

@@ -112,7 +112,7 @@ void make_layout(const spd_model_config &c, Layout &L) {
                      gemm_batch_scratch_bytes(d, F), gemm_batch_scratch_bytes(V, d)})
         pb = b > pb ? b : pb;
     L.part = take(pb);
-    L.arrive = take(1024 * 4);
+    L.arrive = take((size_t)kBatchMaxTileGroups * 4);
     L.zero = take(1024);
     L.ws_total = off;
 }
@@ -331,6 +331,7 @@ int32_t spd_model_set_tuning(spd_model *m, const spd_tuning *t) {
         const int w = t->gemm_waves[i];
         if (w != 0 && w != 4 && w != 8 && w != 16) return fail(SPD_ERR_INVALID_ARG, "gemm_waves must be 0, 4, 8 or 16");
         if (t->gemm_grid_cap[i] < 0 || t->gemm_grid_cap[i] > 65535) return fail(SPD_ERR_INVALID_ARG, "gemm_grid_cap out of range");
+        if (t->gemm_ring[i] != 0 && t->gemm_ring[i] != 8 && t->gemm_ring[i] != 16) return fail(SPD_ERR_INVALID_ARG, "gemm_ring must be 0, 8 or 16");
     }
     const spd_model_config &c = m->cfg;
     const int d = c.d_model, HD = c.n_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
@@ -339,6 +340,7 @@ int32_t spd_model_set_tuning(spd_model *m, const spd_tuning *t) {
         *gt[i] = default_tuning(Ns[i], Ks[i]);
         if (t->gemm_waves[i]) gt[i]->waves = t->gemm_waves[i];
         gt[i]->grid_cap = t->gemm_grid_cap[i];
+        if (t->gemm_ring[i]) gt[i]->ring = t->gemm_ring[i];
         gt[i]->no_regb = t->gemm_general_kernel[i] ? 1 : 0;
         gt[i]->no_batch = t->batch_kernel == 2 ? 1 : 0;
         gt[i]->force_batch = t->batch_kernel == 1 ? 1 : 0;

@@ -26,7 +26,7 @@ EXPORTS = ["spd_last_error", "spd_model_bytes", "spd_model_create", "spd_model_d
            "spd_kv_get_len", "spd_prefill", "spd_prefill_tokens", "spd_verify_forward", "spd_draft_step",
            "spd_accept_workspace_bytes", "spd_speculative_accept", "spd_trace_enable", "spd_trace_read",
            "spd_model_set_tuning", "spd_kv_lens_to_device", "spd_kv_lens_from_device", "spd_draft_step_strided",
-           "spd_block_finish", "spd_device_status", "spd_speculative_accept_static", "spd_kv_export"]
+           "spd_block_finish", "spd_device_status", "spd_speculative_accept_static", "spd_kv_export", "spd_probe_read_chain"]
 TRACE_KINDS = ["qkv", "o", "gate_up", "down", "lm_head", "attention", "embed"]
 PROJECTIONS = ["qkv", "o", "gate_up", "down", "lm_head"]
 
@@ -48,7 +48,7 @@ class spd_model_config(ctypes.Structure):
 class spd_tuning(ctypes.Structure):
     _fields_ = [("separate_qkv_attention", ctypes.c_int32), ("attention_slices", ctypes.c_int32),
                 ("gemm_waves", ctypes.c_int32 * 5), ("gemm_grid_cap", ctypes.c_int32 * 5),
-                ("gemm_general_kernel", ctypes.c_int32 * 5), ("batch_kernel", ctypes.c_int32),
+                ("gemm_general_kernel", ctypes.c_int32 * 5), ("gemm_ring", ctypes.c_int32 * 5), ("batch_kernel", ctypes.c_int32),
                 ("wait_spin_limit", ctypes.c_uint32)]
 
 
@@ -80,6 +80,7 @@ _lib.spd_draft_step.argtypes = [_vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp, _vp]
 _lib.spd_accept_workspace_bytes.argtypes = [_i32, _i32, _i32, _szp]
 _lib.spd_speculative_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _u32, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.spd_speculative_accept_static.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _u32, _vp, _vp, _vp, _vp]
+_lib.spd_probe_read_chain.argtypes = [_vp, _sz, _szp, _i32, _i32, _vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), _vp]
 _lib.spd_trace_enable.argtypes = [_vp, _i32]
 _lib.spd_trace_read.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i32)]
 _lib.spd_kv_lens_to_device.argtypes = [_vp, _vp]
@@ -173,12 +174,13 @@ class Model:
 
     # --- thin wrappers, same names as the C entry points ---------------------------------
     def spd_model_set_tuning(self, separate_qkv_attention=0, attention_slices=0, gemm_waves=None, gemm_grid_cap=None,
-                             gemm_general_kernel=None, batch_kernel=0, wait_spin_limit=0):
+                             gemm_general_kernel=None, gemm_ring=None, batch_kernel=0, wait_spin_limit=0):
         """Kernel-selection knobs for tests and sweeps; the per-projection dicts are keyed by PROJECTIONS."""
         t = spd_tuning()
         t.separate_qkv_attention, t.attention_slices, t.wait_spin_limit = int(separate_qkv_attention), int(attention_slices), int(wait_spin_limit)
         t.batch_kernel = int(batch_kernel)
-        for field, given in (("gemm_waves", gemm_waves), ("gemm_grid_cap", gemm_grid_cap), ("gemm_general_kernel", gemm_general_kernel)):
+        for field, given in (("gemm_waves", gemm_waves), ("gemm_grid_cap", gemm_grid_cap), ("gemm_general_kernel", gemm_general_kernel),
+                             ("gemm_ring", gemm_ring)):
             for name, value in (given or {}).items():
                 getattr(t, field)[PROJECTIONS.index(name)] = int(value)
         _check(_lib.spd_model_set_tuning(self.handle, ctypes.byref(t)))
@@ -296,3 +298,14 @@ def spd_speculative_accept_static(target, draft, draft_tokens, u, temperature, f
                                               _ptr(draft_tokens, torch.int32), _ptr(u, torch.float32), n_seqs, gamma, vocab,
                                               float(temperature), int(flags), _ptr(n_accepted_out, torch.int32),
                                               _ptr(next_token_out, torch.int32), _ptr(accept_prob_out, torch.float32), _stream()))
+
+
+def spd_probe_read_chain(buffer, stage_bytes, reps=20):
+    """(per-kernel microseconds, microseconds per chain) of plain read kernels of the given sizes over `buffer` (a uint8 device tensor)."""
+    n = len(stage_bytes)
+    sizes = (ctypes.c_size_t * n)(*[int(b) for b in stage_bytes])
+    sink = torch.zeros(1024, dtype=torch.int32, device=buffer.device)
+    us = (ctypes.c_double * n)()
+    chain = ctypes.c_double()
+    _check(_lib.spd_probe_read_chain(_ptr(buffer, torch.uint8), buffer.numel(), sizes, n, int(reps), _ptr(sink), us, ctypes.byref(chain), _stream()))
+    return list(us), chain.value

@@ -120,6 +120,7 @@ def test_null_handles_are_refused_by_every_entry_point():
         "spd_trace_enable": (null, i32(1)),
         "spd_trace_read": (null, i32(8), null, null),
         "spd_model_set_tuning": (null, null),
+        "spd_probe_read_chain": (null, sz(0), null, i32(1), i32(1), null, null, null, null),
     }
     for name, args in calls.items():
         fn = getattr(lib, name)
