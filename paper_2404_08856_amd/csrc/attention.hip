@@ -19,7 +19,7 @@ hipError_t launch_attention(const AttnArgs &a, hipStream_t stream) {
     // cost (8 sequences, context 2048: 73 us per layer unsliced, 76 with 2, 108 with 4, 160 with 8 slices;
     // context 640, 5 queries, 32 heads: 3 sequences 17.8 us with 2 slices against 24.2 with 4, 5 sequences
     // 22.3 unsliced against 28.9 with 2): the largest count that keeps pairs * slices within the 256 CUs.
-    // a.slices (a tuning knob for tests and sweeps) overrides for head_dim 128.
+    // a.slices (a tuning knob for tests and sweeps) overrides; 64-wide heads have at most 4 slices.
     int slices = a.slices;
     const int pairs = a.n_seqs * a.H;
     if (slices != 1 && slices != 2 && slices != 4 && slices != 8) slices = pairs > 128 ? 1 : (pairs > 64 ? 2 : (pairs > 32 ? 4 : 8));
@@ -40,8 +40,12 @@ hipError_t launch_attention(const AttnArgs &a, hipStream_t stream) {
         SPD_ATTN(128, 4, kAttnWaves);
     } else if (a.dh == 128) {
         SPD_ATTN(128, 8, kAttnWaves);
-    } else if (a.dh == 64) {
+    } else if (a.dh == 64 && slices >= 4) {
         SPD_ATTN(64, 4, kAttnWaves);
+    } else if (a.dh == 64 && slices == 2) {
+        SPD_ATTN(64, 2, kAttnWaves);
+    } else if (a.dh == 64) {
+        SPD_ATTN(64, 1, kAttnWaves);
     } else {
         return hipErrorInvalidValue;
     }

@@ -945,6 +945,8 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStre
         const int g1 = pick_grid(k.n_tiles, tune.grid_cap > 0 ? tune.grid_cap : 256);
         if (waves == 16 && k.KS == 16 * 8) return launch_regb<16, 8, 8, 2>(k, epilogue, g1, stream);
         if (k.KS == 8 * 16) return launch_regb<8, 16, 8, 2>(k, epilogue, g1, stream);
+        if (waves == 8 && k.KS == 8 * 8) return launch_regb<8, 8, 8, 2>(k, epilogue, g1, stream);
+        if (waves == 4 && k.KS == 4 * 8) return launch_regb<4, 8, 8, 2>(k, epilogue, pick_grid(k.n_tiles, tune.grid_cap > 0 ? tune.grid_cap : 512), stream);
     }
 #define SPD_GEMM_CASE(NG_, W_, U_) return launch_epi<NG_, W_, U_>(k, epilogue, grid, stream)
     if (groups == 1) {
@@ -955,6 +957,13 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, GemmTuning tune, hipStre
         if (waves == 4) SPD_GEMM_CASE(1, 4, 8);
         if (waves == 8) SPD_GEMM_CASE(1, 8, 8);
         SPD_GEMM_CASE(1, 16, 8);
+    }
+    // rows 6..10 on a matrix with few tiles (the draft models' projections at 6..10 sequences): the general kernel with
+    // both groups' activation blocks riding in the ring beats the K-splitting kernel below (d = 768: QKV 7.1 against
+    // 8.6 us, O 6.5 / 8.8, down 9.3 / 12.0); from 256 tiles on it is the other way round (LM head 21.5 / 17.9)
+    if (groups == 2 && k.n_tiles < 256) {
+        if (waves == 4) SPD_GEMM_CASE(2, 4, 8);
+        SPD_GEMM_CASE(2, 8, 8);
     }
 #undef SPD_GEMM_CASE
     // More than 10 rows with a scratch buffer: the tile-splitting kernel makes one pass over the weights for up to 13

@@ -532,6 +532,31 @@ def test_attention_head_slicing_variants(slices):
     model.close()
 
 
+@pytest.mark.parametrize("slices", [1, 2, 4])
+def test_attention_head_slicing_variants_at_head_dim_64(slices):
+    """The same for 64-wide heads (the 12 x 64 draft): 1, 2 or 4 slices, 3 sequences of ragged length, 5 and 7 rows."""
+    shape = synth.ModelShape(1, 256, 4, 64, 344, 1024)
+    print(f"case head_dim 64 slices={slices}", flush=True)
+    for rows in (5, 7):
+        model, wn = build_pair(shape, 62, 3, 160)
+        model.spd_model_set_tuning(attention_slices=slices)
+        cfg = oracle_cfg(shape)
+        caches = []
+        for s in range(3):
+            toks = synth.text_tokens(31 + 47 * s, shape.vocab, 710 + s)      # 31, 78, 125 cached positions
+            c = dec.KVCache(cfg, 160)
+            dec.forward_tokens(cfg, wn, c, toks)
+            caches.append(c)
+            model.spd_prefill_tokens(s, torch.from_numpy(toks).cuda())
+        vt = np.stack([synth.text_tokens(rows, shape.vocab, 810 + s) for s in range(3)])
+        out = torch.empty((3, rows, shape.vocab), dtype=torch.float32, device="cuda")
+        model.spd_verify_forward(torch.from_numpy(vt).cuda(), out)
+        got = out.cpu().numpy()
+        for s in range(3):
+            check_logits(got[s], dec.forward_tokens(cfg, wn, caches[s], vt[s]), f"rows {rows} seq {s}")
+        model.close()
+
+
 def test_tracing_counts_every_launch_group():
     """spd_trace_read: per-kind launch counts of a traced forward (the figures bench.py's roofline uses)."""
     spd = spd_mod()
