@@ -405,13 +405,14 @@ static hipError_t launch_multi(const GemmKernelArgs &k, int epilogue, int grid, 
 // cross workgroups (and XCDs, each with its own L2) inside one launch: device-scope stores, acknowledged
 // before the arrival is counted, and device-scope loads.
 constexpr int kBatchWaves = 8, kBatchMaxJ = 8;
-constexpr int kBatchCH = 4;      // K-steps per activation chunk: two LDS buffers of NG * CH KiB each
+constexpr int kBatchCH = 4;      // K-steps per activation chunk: every LDS buffer holds NG * CH KiB
 // chunks the weight ring runs ahead (registers: TT * RDC * CH * 4 for the ring next to TT * NG * 4 accumulators)
 constexpr int batch_ring_chunks(int NG, int TT) { return (TT * NG * 4 + TT * 2 * kBatchCH * 4 <= 144) ? 2 : 1; }
 
 struct BatchPlan { int TT, J, n_tgroups; };
-// TT tiles per wave (accumulators = TT * NG * 4 VGPRs, weight ring = TT * CH blocks in flight per wave); J K-slices (at most 8: the last arriver reads J partials per
-// output) so that there is about one workgroup per CU: the J in range with the shortest longest slice.
+// TT tiles per wave (accumulators = TT * NG * 4 VGPRs, weight ring = TT * CH blocks in flight per wave and ring
+// chunk); J K-slices (at most 8: the last arriver reads J partials per output) so that there is about one
+// workgroup per CU: the J in range with the shortest longest slice.
 static BatchPlan batch_plan(int n_tiles, int KS, int NG, int tt = 0) {
     BatchPlan p;
     // Measured at the 7B shapes: one tile per wave beats two everywhere (40 rows: 5.31 against 5.45 ms per step, 20 rows:
