@@ -50,6 +50,16 @@ def parse():
     return ap.parse_args()
 
 
+def settle(torch, fn, seconds=0.3):
+    """Untimed repetitions of fn for `seconds` of wall time: the device needs about 0.2 s of continuous work to reach
+    its steady clocks (a region timed right after an idle gap reads 4 % slow)."""
+    t0 = time.time()
+    while time.time() - t0 < seconds:
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+
+
 def cpu_baseline(shape, w_host, kv_host, n_prefix, vt_host, reps=3):
     """The CPU oracle's verify step as it stands (float64 numpy; it widens every bf16 matrix on the fly) over ALL
     layers of the model, against the very prefix the GPU step ran on (the device's KV cache read back: bf16
@@ -109,9 +119,7 @@ def side_configs(args, spd, synth, torch):
         for j in range(args.gamma):                 # the sampled token feeds the next step on the device
             dm.spd_draft_step(tok.view(1, 1), 1.0, ud[j:j + 1], D, tok)
 
-    for _ in range(5):
-        draft_block()
-    torch.cuda.synchronize()
+    settle(torch, draft_block)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     reps = 50
     e0.record()
@@ -152,9 +160,7 @@ def side_configs(args, spd, synth, torch):
         for j in range(args.gamma):
             pm.spd_draft_step(tok.view(1, 1), 1.0, ud[j:j + 1], D, tok)
 
-    for _ in range(5):
-        paper_block()
-    torch.cuda.synchronize()
+    settle(torch, paper_block)
     e0.record()
     for _ in range(reps):
         paper_block()
@@ -178,9 +184,7 @@ def side_configs(args, spd, synth, torch):
         k = torch.empty(n_seqs, dtype=torch.int32, device="cuda")
         y = torch.empty(n_seqs, dtype=torch.int32, device="cuda")
         ws = torch.empty(spd.spd_accept_workspace_bytes(n_seqs, args.gamma, V), dtype=torch.uint8, device="cuda")
-        for _ in range(5):
-            spd.spd_speculative_accept(lt, ld, dtok, u, 1.0, 0, k, y, None, ws)
-        torch.cuda.synchronize()
+        settle(torch, lambda: spd.spd_speculative_accept(lt, ld, dtok, u, 1.0, 0, k, y, None, ws))
         e0.record()
         for _ in range(reps):
             spd.spd_speculative_accept(lt, ld, dtok, u, 1.0, 0, k, y, None, ws)
@@ -514,9 +518,7 @@ def batched_verify(args, spd, synth, torch):
             model.spd_kv_set_len([n_prefix] * B)
             model.spd_verify_forward(vt, out)
 
-        for _ in range(3):
-            step()
-        torch.cuda.synchronize()
+        settle(torch, step)
         reps = 20
         e0.record()
         for _ in range(reps):
@@ -534,9 +536,7 @@ def batched_verify(args, spd, synth, torch):
             model.spd_kv_set_len([n_prefix])
             model.spd_verify_forward(vt, out)
 
-        for _ in range(3):
-            step_g()
-        torch.cuda.synchronize()
+        settle(torch, step_g)
         e0.record()
         for _ in range(20):
             step_g()
@@ -606,6 +606,7 @@ def main():
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
     def timed(fn):
+        settle(torch, fn)                           # clocks up before the W warm-up steps (reported as "settle_s")
         for _ in range(args.warmup):
             fn()
         torch.cuda.synchronize()
@@ -700,7 +701,7 @@ def main():
                                f"KV prefix {args.image_rows} image rows + {args.text_tokens} text tokens, gamma+1={M} tokens, batch {B}, "
                                "then speculative accept (logit inputs, temperature 1)",
                    "n_layers": shape.n_layers, "gamma": args.gamma, "prefix_positions": n_prefix, "batch": B},
-        "launch": launch, "ms_per_step_eager": eager_ms, "ms_per_step_graph": graph_ms,
+        "launch": launch, "ms_per_step_eager": eager_ms, "ms_per_step_graph": graph_ms, "settle_s": 0.3,
         "hbm_GBps": gbps, "hbm_frac_of_peak": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_step": step_bytes,
         "roofline": {"bound": "hbm", "kernel": dom_name,
                      "achieved": dom_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": dom_gbps / HBM_PEAK_GBPS,
