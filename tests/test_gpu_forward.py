@@ -557,6 +557,39 @@ def test_attention_head_slicing_variants_at_head_dim_64(slices):
         model.close()
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_seeded_random_shapes_rows_and_kernel_choices(seed):
+    """Eight one-layer models per seed with widths, head counts, intermediate sizes and vocabularies drawn at random
+    (tile counts that are no multiple of a tile group, K ranges that are no multiple of a chunk), 1..8 sequences of
+    1..8 rows over ragged prefixes, every batched-kernel choice: logits against the oracle."""
+    import random
+    rng = random.Random(seed)
+    for case in range(8):
+        dh = rng.choice([64, 128])
+        shape = synth.ModelShape(1, rng.choice([256, 384, 512, 768, 1024, 1536, 2048, 4096]), rng.choice([1, 2, 3, 4, 6, 8]), dh,
+                                 16 * rng.randint(8, 300), 16 * rng.randint(20, 300))
+        n_seqs, M, bk = rng.randint(1, 8), rng.randint(1, 8), rng.choice([0, 1, 2])
+        print(f"case seed={seed}/{case}: {shape} n_seqs={n_seqs} M={M} batch_kernel={bk}", flush=True)
+        model, wn = build_pair(shape, 900 + case, n_seqs, 64)
+        model.spd_model_set_tuning(batch_kernel=bk)
+        cfg = oracle_cfg(shape)
+        caches = []
+        for s in range(n_seqs):
+            toks = synth.text_tokens(1 + rng.randint(0, 40), shape.vocab, 500 + s)
+            c = dec.KVCache(cfg, 64)
+            dec.forward_tokens(cfg, wn, c, toks)
+            caches.append(c)
+            model.spd_prefill_tokens(s, torch.from_numpy(toks).cuda())
+        vt = np.stack([synth.text_tokens(M, shape.vocab, 600 + s) for s in range(n_seqs)])
+        out = torch.empty((n_seqs, M, shape.vocab), dtype=torch.float32, device="cuda")
+        model.spd_verify_forward(torch.from_numpy(vt).cuda(), out)
+        got = out.cpu().numpy()
+        for s in range(n_seqs):
+            check_logits(got[s], dec.forward_tokens(cfg, wn, caches[s], vt[s]), f"case {case} seq {s}")
+        model.spd_device_status()
+        model.close()
+
+
 def test_tracing_counts_every_launch_group():
     """spd_trace_read: per-kind launch counts of a traced forward (the figures bench.py's roofline uses)."""
     spd = spd_mod()
