@@ -124,3 +124,70 @@ def test_wait_spin_limit_is_reported_and_every_kernel_exits():
             break
     assert tripped
     model.close()
+
+
+def test_batched_projection_kernel_graph_replays_match_the_oracle():
+    """The batched projection kernel keeps its arrival counters on the device (the last arriver of a tile group
+    clears its counter), so a captured 20-row call can be replayed any number of times: 4 sequences x 5 rows on a
+    model with K-sliced matrices (d_model 4096), new tokens before every replay, eager calls in between."""
+    from paper_2404_08856_amd import spd
+    shape = synth.ModelShape(1, 4096, 2, 128, 3072, 1024)
+    n_seqs, M, cap = 4, 5, 48
+    print("case batched kernel graph replay", flush=True)
+    w = randomize_gains(synth.make_weights(shape, 58))
+    model = spd.Model(spd.make_config(shape, n_seqs, cap), to_device(w))
+    model.spd_model_set_tuning(batch_kernel=1)
+    wn = synth.weights_to_numpy(w)
+    del w
+    cfg = oracle_cfg(shape)
+    caches, lens = [], []
+    for s in range(n_seqs):
+        toks = synth.text_tokens(3 + 4 * s, shape.vocab, 500 + s)
+        c = dec.KVCache(cfg, cap)
+        dec.forward_tokens(cfg, wn, c, toks)
+        caches.append(c)
+        lens.append(len(toks))
+        model.spd_prefill_tokens(s, torch.from_numpy(toks).cuda())
+    vt = torch.zeros((n_seqs, M), dtype=torch.int32, device="cuda")
+    out = torch.empty((n_seqs, M, shape.vocab), dtype=torch.float32, device="cuda")
+
+    def check(toks, what):
+        got = out.cpu().numpy()
+        for s in range(n_seqs):
+            caches[s].truncate(lens[s])
+            check_logits(got[s], dec.forward_tokens(cfg, wn, caches[s], toks[s]), f"{what} seq {s}")
+
+    def run_eager(seed, what):
+        toks = synth.text_tokens(n_seqs * M, shape.vocab, seed).reshape(n_seqs, M)
+        vt.copy_(torch.from_numpy(toks))
+        model.spd_kv_set_len(lens)
+        out.zero_()
+        model.spd_verify_forward(vt, out)
+        torch.cuda.synchronize()
+        check(toks, what)
+
+    run_eager(3000, "eager before capture")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        model.spd_kv_set_len(lens)
+        model.spd_verify_forward(vt, out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    model.spd_kv_set_len(lens)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        model.spd_verify_forward(vt, out)
+    run_eager(3100, "eager right after the capture")
+    for rep in range(4):
+        toks = synth.text_tokens(n_seqs * M, shape.vocab, 3200 + rep).reshape(n_seqs, M)
+        vt.copy_(torch.from_numpy(toks))
+        model.spd_kv_set_len(lens)                      # host-side lengths: the captured call reads them at capture time
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        check(toks, f"replay {rep}")
+        if rep % 2 == 0:
+            run_eager(3300 + rep, f"eager between replays {rep}")
+    model.spd_device_status()
+    model.close()
