@@ -22,8 +22,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # HBM bytes per launch of the gate|up projection kernel at the 7B shape, from the two
 # rocprofv3 --pmc runs summarised in profiles/verify_step_llama7b_hbm_traffic.txt
-# (FETCH_SIZE 88628.0 KiB x 2.0 + WRITE_SIZE 344.0 KiB x 1.0; factors from a 1 GiB copy)
-GATE_UP_7B_TRAFFIC_BYTES = int((88628.0 * 2.0 + 344.0) * 1024)
+# (FETCH_SIZE 88625.0 KiB x 2.0 + WRITE_SIZE 344.0 KiB x 1.0; factors from a 1 GiB copy)
+GATE_UP_7B_TRAFFIC_BYTES = int((88625.0 * 2.0 + 344.0) * 1024)
 
 
 def parse():
